@@ -1,0 +1,141 @@
+"""Benchmark: full ASNN activation on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--flags 0] [--no-cpu]
+
+A step is one asnn_activate call: every level of the packed network for the
+whole batch (input staging, gather-FMA-sigmoid per level, output extraction),
+graph and inputs resident in HBM.  Prints ONE JSON line: whole-job throughput
+in G edge*samples/s, the roofline of the dominant kernel from HIP-event
+timings of the level launches, and the CPU oracle timed on this host.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E bandwidth
+
+
+def algorithmic_bytes(n_nodes, n_edges, n_inputs, B, level0_rows):
+    """Gather model of one activation: every connection fetches one fp32 of
+    its source per sample and its (col, w) pair once; every node value is
+    written once; row_ptr is read once; the inputs are read once."""
+    gather = 4.0 * n_edges * B
+    store = 4.0 * n_nodes * B
+    csr = 8.0 * n_edges + 4.0 * n_nodes
+    inputs = 4.0 * n_inputs * B
+    return gather + store + csr + inputs
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=3)
+    ap.add_argument("--flags", type=int, default=0, help="asnn_activate flags (2 = fp32 accumulate)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; samples and networks shard without any exchange "
+              "(see DESIGN.md), but no multi-GPU figure is produced here. Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2005_04347_amd as amd
+    from workloads import make_config
+
+    amd.load()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    wl = make_config(args.config, "full")
+    t0 = time.perf_counter()
+    net = amd.Network(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.output_ids, device=dev)
+    torch.cuda.synchronize()
+    prep_ms = (time.perf_counter() - t0) * 1e3
+    X = torch.from_numpy(wl.X).to(dev)
+    B = wl.B
+    V = torch.empty((wl.n_nodes, B), dtype=torch.float32, device=dev)
+    Y = torch.empty((len(wl.output_ids), B), dtype=torch.float32, device=dev)
+
+    def step():
+        net.activate(X, V=V, Y=Y, flags=args.flags)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # whole-step timing: wall clock around K steps bracketed by synchronisation
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # kernel-only timing with HIP events on the launch stream (same stream the
+    # library launches on): events bracket each step, so the figure is the
+    # device time of all level launches of one activation, launch gaps included
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for a, b in ev:
+        a.record()
+        step()
+        b.record()
+    torch.cuda.synchronize()
+    dev_ms = sorted(a.elapsed_time(b) for a, b in ev)
+    dev_ms_med = dev_ms[len(dev_ms) // 2]
+
+    edge_samples = float(wl.n_edges) * B
+    value = edge_samples / (wall_ms * 1e-3) / 1e9
+    lp = net.graph.level_ptr_host
+    alg_bytes = algorithmic_bytes(wl.n_nodes, wl.n_edges, len(wl.input_ids), B, int(lp[2]))
+    achieved = alg_bytes / (dev_ms_med * 1e-3) / 1e9
+    out = {
+        "metric": "G edge*samples/s for full ASNN activation",
+        "value": round(value, 3),
+        "unit": "G edge*samples/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(wall_ms, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32" if (args.flags & 2) else "f64",
+        "data": "synthetic",
+        "config": {"workload": f"config{args.config}:{wl.name}", "n_nodes": wl.n_nodes, "n_edges": wl.n_edges,
+                   "n_levels": net.n_levels, "batch": B, "n_nets": wl.n_nets, "flags": args.flags,
+                   "preprocess_ms_first_call": round(prep_ms, 2)},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "kernel": "gather_level_kernel (all level launches of one activation)",
+                     "algorithmic_bytes_per_step": alg_bytes, "device_ms_per_step_median": round(dev_ms_med, 4),
+                     "device_ms_per_step_min": round(dev_ms[0], 4)},
+    }
+    if not args.no_cpu:
+        import oracle
+        cols = min(B, 64)
+        Xs = np.ascontiguousarray(wl.X[:, :cols])
+        oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, Xs[:, :1])        # warm-up
+        t0 = time.perf_counter()
+        oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, Xs)
+        cpu_s = time.perf_counter() - t0
+        out["cpu_baseline"] = {
+            "value": round(float(wl.n_edges) * cols / cpu_s / 1e9, 4), "unit": "G edge*samples/s", "cores": 1,
+            "kind": "oracle",
+            "sample": f"the same network, first {cols} of {B} batch columns (columns are independent), "
+                      f"{cpu_s:.2f} s single-threaded on {os.cpu_count()} visible host cores",
+        }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,143 @@
+/*
+ * libasnn -- full forward activation of arbitrary-structure sparse neural
+ * networks (ASNNs) on one AMD MI355X (gfx950).  C ABI.
+ *
+ * An ASNN is a directed acyclic graph: N nodes, E weighted connections
+ * (src[e] -> dst[e], w[e]), a set of input ("sensor") nodes.  The library
+ *   1. assigns every node its dependency layer ("level"): the paper's
+ *      network segmentation (Sec. "Sequential activation", segmentation
+ *      algorithm) -- a node enters the next layer once its entire input set is
+ *      assigned, i.e. level = longest path from any node without incoming
+ *      connections; the input layer is level 0 (Sec. "Parallel GPU activation");
+ *   2. packs the network into a destination-sorted CSR whose nodes are ordered
+ *      by level (the paper sorts its node array by layer number and keeps the
+ *      per-layer node counts NNL, Sec. "Parallel GPU activation");
+ *   3. activates the network level by level for a batch of B input vectors:
+ *      sensors output sigmoid(x), every other node outputs
+ *      sigmoid(sum_i w_i * value(in_i)) with sigmoid(x) = 1/(1+e^(-4.97 x))
+ *      (Introduction, display equation; activation kernel listing).  A node
+ *      with no incoming connection that is no sensor outputs sigmoid(0) = 0.5.
+ *
+ * Conventions
+ *   - "device" pointers are HIP device memory on the current device; "host"
+ *     pointers are ordinary host memory.  The library never takes ownership of
+ *     a caller's buffer and never returns memory the caller must free.
+ *   - stream is a hipStream_t passed as void* (NULL = the default stream).
+ *     asnn_build_levels and asnn_pack_csr synchronise that stream before they
+ *     return (they hand scalars / small arrays back to the host).
+ *     asnn_activate only enqueues work and returns.
+ *   - every function returns ASNN_OK (0) or a negative ASNN_ERR_* code; nothing
+ *     is printed, thrown or aborted.  asnn_last_hip_error() holds the hipError_t
+ *     behind the most recent ASNN_ERR_HIP on the calling thread.
+ *   - parallel connections (a,b) are legal and their contributions add; a self
+ *     loop is a cycle; node ids need not be in topological order.
+ *   - batch layout is node-major with the batch contiguous: X[k*B + b],
+ *     V[i*B + b], Y[o*B + b].
+ */
+#ifndef ASNN_H
+#define ASNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ASNN_OK 0
+#define ASNN_ERR_NULL (-1)               /* a required pointer is NULL */
+#define ASNN_ERR_SIZE (-2)               /* negative / zero / too large size argument */
+#define ASNN_ERR_INDEX (-3)              /* src, dst, input or level value out of range */
+#define ASNN_ERR_INPUT_HAS_INEDGE (-4)   /* a connection ends in an input node */
+#define ASNN_ERR_DUP_INPUT (-5)          /* an input id is listed twice */
+#define ASNN_ERR_CYCLE (-6)              /* the connections contain a cycle */
+#define ASNN_ERR_WORKSPACE (-7)          /* workspace too small or misaligned */
+#define ASNN_ERR_HIP (-8)                /* a HIP runtime call failed */
+#define ASNN_ERR_LEVEL_ORDER (-9)        /* level[] is not increasing along a connection */
+#define ASNN_ERR_NO_DEVICE (-10)         /* no HIP device available */
+
+/* asnn_activate flags */
+#define ASNN_FLAG_RAW_INPUTS 1u  /* store sensor inputs unsquashed (the paper squashes them) */
+#define ASNN_FLAG_ACC_F32 2u     /* accumulate and squash in fp32 (default: fp64 accumulate and
+                                    fp64 sigmoid, rounded once to fp32 on store) */
+
+/* Nodes with at least this many incoming connections are "heavy": inside a
+ * level the packed order lists them first (see asnn_pack_csr). */
+#define ASNN_HEAVY_INDEGREE 512
+
+const char *asnn_strerror(int code);
+int asnn_last_hip_error(void);
+int asnn_version(void);
+
+/* ---- 1. levels ---------------------------------------------------------
+ * Segmentation into dependency layers (segmentation algorithm; reading: every
+ * node without incoming connections is in layer 0, sensor or not).
+ *   src, dst     device int32[n_edges]   connection e goes src[e] -> dst[e]
+ *   input_ids    device int32[n_inputs]  the sensor nodes (may be NULL if n_inputs == 0)
+ *   level_out    device int32[n_nodes]   receives the level of every node
+ *   n_levels_out host   int32*           receives max level + 1 (0 if n_nodes == 0)
+ *   workspace    device, >= asnn_levels_workspace_bytes(), 256-byte aligned
+ * Errors: NULL, SIZE (n_nodes < 0, n_edges < 0 or >= 2^31), INDEX,
+ * INPUT_HAS_INEDGE, DUP_INPUT, CYCLE (level_out is then unspecified),
+ * WORKSPACE, HIP.  Blocks until the result is known. */
+size_t asnn_levels_workspace_bytes(int32_t n_nodes, int64_t n_edges);
+int asnn_build_levels(int32_t n_nodes, int64_t n_edges,
+                      const int32_t *src, const int32_t *dst,
+                      const int32_t *input_ids, int32_t n_inputs,
+                      int32_t *level_out, int32_t *n_levels_out,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---- 2. pack -----------------------------------------------------------
+ * Level-contiguous, destination-sorted CSR (replaces the paper's per-node
+ * record with its inNodes / inWeights arrays and the array sorted by layer).
+ * Packed order: by level; inside a level the heavy nodes (in-degree >=
+ * ASNN_HEAVY_INDEGREE) first, then the rest; ties by original id.  The
+ * connections of one node keep their edge-list order.
+ *   level          device int32[n_nodes]      from asnn_build_levels
+ *   level_ptr      device int32[2*n_levels+1] level l: heavy nodes are packed rows
+ *                  [level_ptr[2l], level_ptr[2l+1]), the others [level_ptr[2l+1], level_ptr[2l+2])
+ *   level_ptr_host host   int32[2*n_levels+1] the same numbers for the host
+ *   perm           device int32[n_nodes]      packed row -> original id
+ *   inv_perm       device int32[n_nodes]      original id -> packed row
+ *   row_ptr        device int32[n_nodes+1]    connections of packed row i are [row_ptr[i], row_ptr[i+1])
+ *   col            device int32[n_edges]      packed row of the connection's source
+ *   w_packed       device float[n_edges]
+ *   workspace      device, >= asnn_pack_workspace_bytes(), 256-byte aligned
+ * Errors: NULL, SIZE, INDEX (level outside [0,n_levels), id out of range),
+ * LEVEL_ORDER, WORKSPACE, HIP.  Blocks until level_ptr_host is filled. */
+size_t asnn_pack_workspace_bytes(int32_t n_nodes, int64_t n_edges);
+int asnn_pack_csr(int32_t n_nodes, int64_t n_edges, int32_t n_levels,
+                  const int32_t *src, const int32_t *dst, const float *w, const int32_t *level,
+                  int32_t *level_ptr, int32_t *level_ptr_host,
+                  int32_t *perm, int32_t *inv_perm,
+                  int32_t *row_ptr, int32_t *col, float *w_packed,
+                  void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---- 3. activate -------------------------------------------------------
+ * Level-synchronous full activation of the packed network (or of a packed
+ * disjoint union of networks: a population is activated by one call) for B
+ * input vectors (activation kernel listing; the layer barrier there is the
+ * boundary between two level launches here).
+ *   level_ptr_host host  int32[2*n_levels+1]  from asnn_pack_csr
+ *   row_ptr, col, w_packed, inv_perm  device  from asnn_pack_csr
+ *   input_ids   device int32[n_inputs]  original ids; X row k feeds input_ids[k]
+ *   output_ids  device int32[n_outputs] original ids (may be NULL if Y is NULL)
+ *   X           device float[n_inputs*B]
+ *   V           device float[n_nodes*B]  receives the activation of EVERY node, packed
+ *               row order (row i = node perm[i]); 16-byte aligned
+ *   Y           device float[n_outputs*B] or NULL; receives the rows of output_ids
+ * Ids outside [0,n_nodes) in input_ids / output_ids are skipped (an output row
+ * of such an id is filled with NaN).  Errors: NULL, SIZE, HIP.  Asynchronous. */
+int asnn_activate(int32_t n_nodes, int64_t n_edges, int32_t n_levels,
+                  const int32_t *level_ptr_host,
+                  const int32_t *row_ptr, const int32_t *col, const float *w_packed,
+                  const int32_t *inv_perm,
+                  const int32_t *input_ids, int32_t n_inputs,
+                  const int32_t *output_ids, int32_t n_outputs,
+                  const float *X, int32_t B, float *V, float *Y,
+                  uint32_t flags, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ASNN_H */

@@ -1,0 +1,18 @@
+"""MI355X-native full activation of arbitrary-structure sparse neural networks.
+
+The product is the C-ABI library ``libasnn.so`` (HIP, gfx950; headers in
+``include/asnn.h``, sources in ``csrc/``).  This package is the thin ctypes
+binding above it; build the library with ``python -m paper_2005_04347_amd.build``.
+"""
+from .binding import (  # noqa: F401
+    AsnnError,
+    FLAG_ACC_F32,
+    FLAG_RAW_INPUTS,
+    HEAVY_INDEGREE,
+    Network,
+    PackedGraph,
+    asnn_activate,
+    asnn_build_levels,
+    asnn_pack_csr,
+    load,
+)

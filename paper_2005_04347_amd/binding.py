@@ -1,0 +1,207 @@
+"""ctypes binding for libasnn (see include/asnn.h).
+
+Argument marshalling only: torch tensors provide device memory and the
+current stream; every step of the path runs inside the library's HIP kernels.
+There is no CPU fallback: loading fails loudly when libasnn.so is missing.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libasnn.so")
+
+FLAG_RAW_INPUTS = 1
+FLAG_ACC_F32 = 2
+HEAVY_INDEGREE = 512
+
+ERR_NAMES = {
+    -1: "ASNN_ERR_NULL", -2: "ASNN_ERR_SIZE", -3: "ASNN_ERR_INDEX", -4: "ASNN_ERR_INPUT_HAS_INEDGE",
+    -5: "ASNN_ERR_DUP_INPUT", -6: "ASNN_ERR_CYCLE", -7: "ASNN_ERR_WORKSPACE", -8: "ASNN_ERR_HIP",
+    -9: "ASNN_ERR_LEVEL_ORDER", -10: "ASNN_ERR_NO_DEVICE",
+}
+
+EXPORTS = [
+    "asnn_strerror", "asnn_last_hip_error", "asnn_version",
+    "asnn_levels_workspace_bytes", "asnn_build_levels",
+    "asnn_pack_workspace_bytes", "asnn_pack_csr", "asnn_activate",
+]
+
+
+class AsnnError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        lib = load()
+        msg = lib.asnn_strerror(code).decode()
+        extra = f" (hipError {lib.asnn_last_hip_error()})" if code == -8 else ""
+        super().__init__(f"{where}: {ERR_NAMES.get(code, code)}: {msg}{extra}")
+        self.code = code
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Loads libasnn.so built in-tree (python -m paper_2005_04347_amd.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} not found: build it with `python -m paper_2005_04347_amd.build` "
+                          "(there is no fallback path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, u32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint32, ctypes.c_size_t
+    lib.asnn_strerror.restype = ctypes.c_char_p
+    lib.asnn_strerror.argtypes = [ctypes.c_int]
+    lib.asnn_last_hip_error.restype = ctypes.c_int
+    lib.asnn_last_hip_error.argtypes = []
+    lib.asnn_version.restype = ctypes.c_int
+    lib.asnn_version.argtypes = []
+    lib.asnn_levels_workspace_bytes.restype = sz
+    lib.asnn_levels_workspace_bytes.argtypes = [i32, i64]
+    lib.asnn_build_levels.restype = ctypes.c_int
+    lib.asnn_build_levels.argtypes = [i32, i64, vp, vp, vp, i32, vp, ctypes.POINTER(i32), vp, sz, vp]
+    lib.asnn_pack_workspace_bytes.restype = sz
+    lib.asnn_pack_workspace_bytes.argtypes = [i32, i64]
+    lib.asnn_pack_csr.restype = ctypes.c_int
+    lib.asnn_pack_csr.argtypes = [i32, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.asnn_activate.restype = ctypes.c_int
+    lib.asnn_activate.argtypes = [i32, i64, i32, vp, vp, vp, vp, vp, vp, i32, vp, i32, vp, i32, vp, vp, u32, vp]
+    _lib = lib
+    return lib
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None or t.numel() == 0 else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev_i32(a, device):
+    if isinstance(a, torch.Tensor):
+        return a.to(device=device, dtype=torch.int32).contiguous()
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(device)
+
+
+def _dev_f32(a, device):
+    if isinstance(a, torch.Tensor):
+        return a.to(device=device, dtype=torch.float32).contiguous()
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
+
+
+def _workspace(nbytes: int, device):
+    # torch's caching allocator returns 512-byte aligned blocks
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
+def asnn_build_levels(n_nodes: int, src: torch.Tensor, dst: torch.Tensor, input_ids: torch.Tensor):
+    """-> (level: int32 device tensor [n_nodes], n_levels: int)."""
+    lib = load()
+    device = src.device
+    n_edges = int(src.numel())
+    level = torch.empty(max(n_nodes, 1), dtype=torch.int32, device=device)
+    nbytes = lib.asnn_levels_workspace_bytes(n_nodes, n_edges)
+    ws = _workspace(nbytes, device)
+    n_levels = ctypes.c_int32(-1)
+    rc = lib.asnn_build_levels(n_nodes, n_edges, _ptr(src), _ptr(dst), _ptr(input_ids), int(input_ids.numel()),
+                               ctypes.c_void_p(level.data_ptr()), ctypes.byref(n_levels),
+                               ctypes.c_void_p(ws.data_ptr()), ws.numel(), _stream())
+    if rc != 0:
+        raise AsnnError(rc, "asnn_build_levels")
+    return level[:n_nodes], int(n_levels.value)
+
+
+@dataclass
+class PackedGraph:
+    n_nodes: int
+    n_edges: int
+    n_levels: int
+    level_ptr: torch.Tensor          # device int32 [2*n_levels+1]
+    level_ptr_host: np.ndarray       # host int32 [2*n_levels+1]
+    perm: torch.Tensor               # device int32 [n_nodes]  packed row -> original id
+    inv_perm: torch.Tensor           # device int32 [n_nodes]  original id -> packed row
+    row_ptr: torch.Tensor            # device int32 [n_nodes+1]
+    col: torch.Tensor                # device int32 [n_edges]
+    w: torch.Tensor                  # device float32 [n_edges]
+
+
+def asnn_pack_csr(n_nodes: int, n_levels: int, src, dst, w, level) -> PackedGraph:
+    lib = load()
+    device = src.device
+    n_edges = int(src.numel())
+    nk = 2 * n_levels + 1
+    level_ptr = torch.empty(nk, dtype=torch.int32, device=device)
+    level_ptr_host = np.zeros(nk, dtype=np.int32)
+    perm = torch.empty(n_nodes, dtype=torch.int32, device=device)
+    inv_perm = torch.empty(n_nodes, dtype=torch.int32, device=device)
+    row_ptr = torch.empty(n_nodes + 1, dtype=torch.int32, device=device)
+    col = torch.empty(max(n_edges, 1), dtype=torch.int32, device=device)
+    wp = torch.empty(max(n_edges, 1), dtype=torch.float32, device=device)
+    ws = _workspace(lib.asnn_pack_workspace_bytes(n_nodes, n_edges), device)
+    rc = lib.asnn_pack_csr(n_nodes, n_edges, n_levels, _ptr(src), _ptr(dst), _ptr(w), _ptr(level),
+                           ctypes.c_void_p(level_ptr.data_ptr()), level_ptr_host.ctypes.data_as(ctypes.c_void_p),
+                           ctypes.c_void_p(perm.data_ptr()), ctypes.c_void_p(inv_perm.data_ptr()),
+                           ctypes.c_void_p(row_ptr.data_ptr()), ctypes.c_void_p(col.data_ptr()),
+                           ctypes.c_void_p(wp.data_ptr()), ctypes.c_void_p(ws.data_ptr()), ws.numel(), _stream())
+    if rc != 0:
+        raise AsnnError(rc, "asnn_pack_csr")
+    return PackedGraph(n_nodes, n_edges, n_levels, level_ptr, level_ptr_host, perm, inv_perm, row_ptr,
+                       col[:n_edges], wp[:n_edges])
+
+
+def asnn_activate(g: PackedGraph, input_ids: torch.Tensor, X: torch.Tensor,
+                  output_ids: Optional[torch.Tensor] = None, V: Optional[torch.Tensor] = None,
+                  Y: Optional[torch.Tensor] = None, flags: int = 0):
+    """Enqueues one full activation on the current stream.
+    X: float32 [n_inputs, B].  Returns (V [n_nodes, B] in packed row order, Y [n_outputs, B] or None)."""
+    lib = load()
+    assert X.dim() == 2 and X.dtype == torch.float32 and X.is_contiguous()
+    B = int(X.shape[1])
+    n_in = int(input_ids.numel())
+    assert X.shape[0] == n_in
+    device = X.device
+    if V is None:
+        V = torch.empty((g.n_nodes, B), dtype=torch.float32, device=device)
+    assert V.shape == (g.n_nodes, B) and V.is_contiguous() and V.dtype == torch.float32
+    n_out = 0 if output_ids is None else int(output_ids.numel())
+    if output_ids is not None and Y is None:
+        Y = torch.empty((n_out, B), dtype=torch.float32, device=device)
+    rc = lib.asnn_activate(g.n_nodes, g.n_edges, g.n_levels, g.level_ptr_host.ctypes.data_as(ctypes.c_void_p),
+                           _ptr(g.row_ptr), _ptr(g.col), _ptr(g.w), _ptr(g.inv_perm),
+                           _ptr(input_ids), n_in, _ptr(output_ids), n_out, _ptr(X), B,
+                           ctypes.c_void_p(V.data_ptr()), _ptr(Y), flags, _stream())
+    if rc != 0:
+        raise AsnnError(rc, "asnn_activate")
+    return V, Y
+
+
+class Network:
+    """Convenience wrapper: build levels + pack once, activate many times."""
+
+    def __init__(self, n_nodes, src, dst, w, input_ids, output_ids, device="cuda:0"):
+        self.device = torch.device(device)
+        self.n_nodes = int(n_nodes)
+        self.src = _dev_i32(src, self.device)
+        self.dst = _dev_i32(dst, self.device)
+        self.w_edges = _dev_f32(w, self.device)
+        self.input_ids = _dev_i32(input_ids, self.device)
+        self.output_ids = _dev_i32(output_ids, self.device)
+        with torch.cuda.device(self.device):
+            self.level, self.n_levels = asnn_build_levels(self.n_nodes, self.src, self.dst, self.input_ids)
+            self.graph = asnn_pack_csr(self.n_nodes, self.n_levels, self.src, self.dst, self.w_edges, self.level)
+
+    def activate(self, X, V=None, Y=None, flags: int = 0):
+        X = _dev_f32(X, self.device)
+        with torch.cuda.device(self.device):
+            return asnn_activate(self.graph, self.input_ids, X, self.output_ids, V=V, Y=Y, flags=flags)
+
+    def values_original_order(self, V: torch.Tensor) -> torch.Tensor:
+        """V (packed rows) -> [n_nodes, B] indexed by original node id (plain torch indexing, for tests)."""
+        return V[self.graph.inv_perm.long()]

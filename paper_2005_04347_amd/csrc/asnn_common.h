@@ -1,0 +1,74 @@
+// Internal helpers shared by the libasnn translation units (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "asnn.h"
+
+namespace asnn {
+
+constexpr int kWave = 64;   // CDNA wavefront width
+
+// Records the hipError_t behind ASNN_ERR_HIP for asnn_last_hip_error().
+void set_last_hip_error(hipError_t e);
+
+#define ASNN_HIP_TRY(expr)                          \
+    do {                                            \
+        hipError_t _e = (expr);                     \
+        if (_e != hipSuccess) {                     \
+            ::asnn::set_last_hip_error(_e);         \
+            return ASNN_ERR_HIP;                    \
+        }                                           \
+    } while (0)
+
+#define ASNN_TRY(expr)                              \
+    do {                                            \
+        int _rc = (expr);                           \
+        if (_rc != ASNN_OK) return _rc;             \
+    } while (0)
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+// Carves 256-byte aligned pieces out of a caller-provided workspace.
+struct Carver {
+    char *base;
+    size_t off = 0;
+    explicit Carver(void *p) : base(static_cast<char *>(p)) {}
+    template <typename T>
+    T *take(size_t count) {
+        T *p = reinterpret_cast<T *>(base + off);
+        off += align_up(count * sizeof(T));
+        return p;
+    }
+};
+
+// ---- device-wide primitives (prims.hip) --------------------------------
+// Exclusive prefix sum of n int32 values; out may alias in.  out[n] is NOT
+// written.  tmp must hold scan_tmp_ints(n) ints.
+size_t scan_tmp_ints(size_t n);
+int exclusive_scan_i32(const int32_t *in, int32_t *out, size_t n, int32_t *tmp, hipStream_t s);
+
+// Stable LSD radix sort of (key, value) pairs on the low `bits` bits of the
+// key.  Sorted pairs end in keys_out/vals_out (which may be either of the
+// ping-pong buffers: the function reports where).  tmp >= radix_tmp_ints(n).
+size_t radix_tmp_ints(size_t n);
+int radix_sort_pairs_u32(uint32_t *keys_a, uint32_t *vals_a, uint32_t *keys_b, uint32_t *vals_b,
+                         size_t n, int bits, int32_t *tmp, hipStream_t s,
+                         uint32_t **keys_sorted, uint32_t **vals_sorted);
+
+inline int bits_for(uint64_t max_value) {   // number of bits needed to hold max_value
+    int b = 1;
+    while (b < 32 && (max_value >> b) != 0) ++b;
+    return b;
+}
+
+inline unsigned blocks_for(size_t n, unsigned per_block, unsigned cap = 0x7fffffffu) {
+    size_t b = (n + per_block - 1) / per_block;
+    if (b < 1) b = 1;
+    if (b > cap) b = cap;
+    return static_cast<unsigned>(b);
+}
+
+}  // namespace asnn

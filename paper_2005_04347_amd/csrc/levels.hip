@@ -1,0 +1,210 @@
+// asnn_build_levels: dependency layers of an ASNN on the GPU.
+//
+// The paper segments the network on the CPU with a set-based loop that rescans
+// every connection per layer and names GPU segmentation as future work.  The
+// same layers come out of a frontier (Kahn) sweep: a node joins layer k+1 in
+// the sweep that removes its last unassigned predecessor, which is exactly
+// "its entire input set is already assigned" and makes its layer one more
+// than its deepest predecessor.  All arithmetic is integer; the result is
+// unique, so the order in which atomics land does not matter.
+#include "asnn_common.h"
+
+namespace asnn {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kSweepsPerSync = 64;     // frontier sweeps enqueued between two host reads
+constexpr int kGroup = 16;             // lanes that share one frontier node's out-edges
+constexpr unsigned kSweepBlocks = 2048;
+
+// Slots of the small control block in device memory.
+enum Ctl : int {
+    kErr = 0,          // first error code seen (0 = none)
+    kAssigned = 1,     // nodes that received a level so far
+    kLevels = 2,       // number of non-empty frontiers so far
+    kCount0 = 4,       // three rotating frontier sizes: sweep k reads kCount0 + k % 3
+    kCtlInts = 16
+};
+
+__device__ inline void flag_error(int *ctl, int code) { atomicCAS(&ctl[kErr], 0, code); }
+
+__global__ void degree_kernel(const int32_t *__restrict__ src, const int32_t *__restrict__ dst, int64_t n_edges,
+                              int32_t n_nodes, int32_t *indeg, int32_t *outdeg, int *ctl) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n_edges; e += stride) {
+        const int32_t a = src[e], b = dst[e];
+        if (a < 0 || a >= n_nodes || b < 0 || b >= n_nodes) {
+            flag_error(ctl, ASNN_ERR_INDEX);
+            continue;
+        }
+        atomicAdd(&indeg[b], 1);
+        atomicAdd(&outdeg[a], 1);
+    }
+}
+
+__global__ void mark_inputs_kernel(const int32_t *__restrict__ input_ids, int32_t n_inputs, int32_t n_nodes,
+                                   const int32_t *__restrict__ indeg, int32_t *is_input, int *ctl) {
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= n_inputs) return;
+    const int32_t v = input_ids[k];
+    if (v < 0 || v >= n_nodes) { flag_error(ctl, ASNN_ERR_INDEX); return; }
+    if (atomicAdd(&is_input[v], 1) != 0) flag_error(ctl, ASNN_ERR_DUP_INPUT);
+    if (indeg[v] != 0) flag_error(ctl, ASNN_ERR_INPUT_HAS_INEDGE);
+}
+
+// out_dst grouped by source; the order inside a group is irrelevant for levels.
+__global__ void fill_out_kernel(const int32_t *__restrict__ src, const int32_t *__restrict__ dst, int64_t n_edges,
+                                int32_t n_nodes, const int32_t *__restrict__ out_ptr, int32_t *cursor,
+                                int32_t *__restrict__ out_dst) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n_edges; e += stride) {
+        const int32_t a = src[e], b = dst[e];
+        if (a < 0 || a >= n_nodes || b < 0 || b >= n_nodes) continue;   // already flagged
+        const int32_t pos = out_ptr[a] + atomicAdd(&cursor[a], 1);
+        out_dst[pos] = b;
+    }
+}
+
+__global__ void first_frontier_kernel(int32_t n_nodes, const int32_t *__restrict__ indeg, int32_t *__restrict__ level,
+                                      int32_t *__restrict__ frontier, int *ctl) {
+    const int v = blockIdx.x * blockDim.x + threadIdx.x;
+    if (v >= n_nodes) return;
+    if (indeg[v] == 0) {
+        level[v] = 0;
+        frontier[atomicAdd(&ctl[kCount0], 1)] = v;
+    } else {
+        level[v] = -1;
+    }
+}
+
+// One sweep: every node of frontier k releases its out-edges; a destination
+// whose remaining in-degree drops to zero gets level k+1 and joins frontier k+1.
+// A sweep over an empty frontier does nothing, so the host may enqueue more
+// sweeps than the network has layers.
+__global__ __launch_bounds__(kThreads) void sweep_kernel(int k, const int32_t *__restrict__ out_ptr,
+                                                          const int32_t *__restrict__ out_dst, int32_t *indeg,
+                                                          int32_t *__restrict__ level,
+                                                          const int32_t *__restrict__ frontier_in,
+                                                          int32_t *__restrict__ frontier_out, int *ctl) {
+    const int count = ctl[kCount0 + k % 3];
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        ctl[kCount0 + (k + 2) % 3] = 0;          // read by sweep k-1 (finished), filled by sweep k+1
+        if (count > 0) {
+            ctl[kLevels] = k + 1;
+            atomicAdd(&ctl[kAssigned], count);
+        }
+    }
+    if (count == 0) return;
+    int *count_out = &ctl[kCount0 + (k + 1) % 3];
+    const int sub = threadIdx.x % kGroup;
+    const int groups = gridDim.x * (kThreads / kGroup);
+    for (int f = blockIdx.x * (kThreads / kGroup) + threadIdx.x / kGroup; f < count; f += groups) {
+        const int32_t v = frontier_in[f];
+        const int32_t e1 = out_ptr[v + 1];
+        for (int32_t e = out_ptr[v] + sub; e < e1; e += kGroup) {
+            const int32_t u = out_dst[e];
+            if (atomicSub(&indeg[u], 1) == 1) {
+                level[u] = k + 1;
+                frontier_out[atomicAdd(count_out, 1)] = u;
+            }
+        }
+    }
+}
+
+}  // namespace
+
+struct LevelsWorkspace {
+    int *ctl;
+    int32_t *indeg, *out_ptr, *cursor, *is_input, *out_dst, *frontier_a, *frontier_b, *scan_tmp;
+    size_t bytes;
+};
+
+static LevelsWorkspace carve_levels(void *ws, int32_t n_nodes, int64_t n_edges) {
+    Carver c(ws);
+    LevelsWorkspace w;
+    const size_t n = (size_t)n_nodes, e = (size_t)n_edges;
+    w.ctl = c.take<int>(kCtlInts);
+    w.indeg = c.take<int32_t>(n + 1);
+    w.out_ptr = c.take<int32_t>(n + 1);
+    w.cursor = c.take<int32_t>(n + 1);
+    w.is_input = c.take<int32_t>(n + 1);
+    w.out_dst = c.take<int32_t>(e + 1);
+    w.frontier_a = c.take<int32_t>(n + 1);
+    w.frontier_b = c.take<int32_t>(n + 1);
+    w.scan_tmp = c.take<int32_t>(scan_tmp_ints(n + 1));
+    w.bytes = c.off;
+    return w;
+}
+
+}  // namespace asnn
+
+using namespace asnn;
+
+extern "C" size_t asnn_levels_workspace_bytes(int32_t n_nodes, int64_t n_edges) {
+    if (n_nodes < 0 || n_edges < 0) return 0;
+    return carve_levels(nullptr, n_nodes, n_edges).bytes;
+}
+
+extern "C" int asnn_build_levels(int32_t n_nodes, int64_t n_edges, const int32_t *src, const int32_t *dst,
+                                 const int32_t *input_ids, int32_t n_inputs, int32_t *level_out, int32_t *n_levels_out,
+                                 void *workspace, size_t workspace_bytes, void *stream) {
+    if (n_nodes < 0 || n_edges < 0 || n_edges >= (int64_t)INT32_MAX || n_inputs < 0) return ASNN_ERR_SIZE;
+    if (!n_levels_out) return ASNN_ERR_NULL;
+    if (n_nodes == 0) {
+        if (n_edges > 0 || n_inputs > 0) return ASNN_ERR_INDEX;
+        *n_levels_out = 0;
+        return ASNN_OK;
+    }
+    if (!level_out || (n_edges > 0 && (!src || !dst)) || (n_inputs > 0 && !input_ids)) return ASNN_ERR_NULL;
+    if (!workspace) return ASNN_ERR_NULL;
+    if (((uintptr_t)workspace & 255u) != 0 || workspace_bytes < asnn_levels_workspace_bytes(n_nodes, n_edges))
+        return ASNN_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    LevelsWorkspace w = carve_levels(workspace, n_nodes, n_edges);
+
+    // ctl, indeg, out_ptr, cursor and is_input are adjacent: clear them in one go.
+    const size_t clear_bytes = (size_t)((char *)w.out_dst - (char *)w.ctl);
+    ASNN_HIP_TRY(hipMemsetAsync(w.ctl, 0, clear_bytes, s));
+
+    if (n_edges > 0) {
+        hipLaunchKernelGGL(degree_kernel, dim3(blocks_for((size_t)n_edges, kThreads, 65535)), dim3(kThreads), 0, s, src,
+                           dst, n_edges, n_nodes, w.indeg, w.out_ptr, w.ctl);
+        ASNN_HIP_TRY(hipGetLastError());
+    }
+    if (n_inputs > 0) {
+        hipLaunchKernelGGL(mark_inputs_kernel, dim3(blocks_for((size_t)n_inputs, kThreads)), dim3(kThreads), 0, s,
+                           input_ids, n_inputs, n_nodes, (const int32_t *)w.indeg, w.is_input, w.ctl);
+        ASNN_HIP_TRY(hipGetLastError());
+    }
+    // out-degree histogram -> out_ptr (n_nodes + 1 entries; the extra zero yields the total)
+    ASNN_TRY(exclusive_scan_i32(w.out_ptr, w.out_ptr, (size_t)n_nodes + 1, w.scan_tmp, s));
+    if (n_edges > 0) {
+        hipLaunchKernelGGL(fill_out_kernel, dim3(blocks_for((size_t)n_edges, kThreads, 65535)), dim3(kThreads), 0, s,
+                           src, dst, n_edges, n_nodes, (const int32_t *)w.out_ptr, w.cursor, w.out_dst);
+        ASNN_HIP_TRY(hipGetLastError());
+    }
+    hipLaunchKernelGGL(first_frontier_kernel, dim3(blocks_for((size_t)n_nodes, kThreads)), dim3(kThreads), 0, s,
+                       n_nodes, (const int32_t *)w.indeg, level_out, w.frontier_a, w.ctl);
+    ASNN_HIP_TRY(hipGetLastError());
+
+    int host_ctl[kCtlInts];
+    int k = 0;
+    for (;;) {
+        for (int i = 0; i < kSweepsPerSync; ++i, ++k) {
+            const int32_t *fin = (k & 1) ? w.frontier_b : w.frontier_a;
+            int32_t *fout = (k & 1) ? w.frontier_a : w.frontier_b;
+            hipLaunchKernelGGL(sweep_kernel, dim3(kSweepBlocks), dim3(kThreads), 0, s, k, (const int32_t *)w.out_ptr,
+                               (const int32_t *)w.out_dst, w.indeg, level_out, fin, fout, w.ctl);
+            ASNN_HIP_TRY(hipGetLastError());
+        }
+        ASNN_HIP_TRY(hipMemcpyAsync(host_ctl, w.ctl, sizeof(host_ctl), hipMemcpyDeviceToHost, s));
+        ASNN_HIP_TRY(hipStreamSynchronize(s));
+        if (host_ctl[kErr] != 0) return host_ctl[kErr];
+        if (host_ctl[kCount0 + k % 3] == 0) break;      // the frontier the next sweep would read is empty
+        if (k > n_nodes) break;                          // cannot happen: at most n_nodes layers
+    }
+    if (host_ctl[kAssigned] != n_nodes) return ASNN_ERR_CYCLE;
+    *n_levels_out = host_ctl[kLevels];
+    return ASNN_OK;
+}

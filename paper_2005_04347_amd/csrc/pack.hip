@@ -1,0 +1,189 @@
+// asnn_pack_csr: level-contiguous, destination-sorted CSR.
+//
+// The paper keeps one record per node (id, layer, numInNodes, inNodes[],
+// inWeights[]), sorts the record array by layer and keeps the node count of
+// every layer.  The same information is laid out here as flat arrays: nodes
+// renumbered so that a level is a contiguous range of rows ("packed rows"),
+// one CSR over packed rows whose column indices are packed rows too, so the
+// value matrix V[row][batch] is level-contiguous and a level launch touches
+// only rows below its own range.
+//
+// Everything is built from two stable radix sorts (nodes by level key, edges
+// by packed destination) and prefix sums, so the packed arrays are a
+// deterministic function of the input: a node's connections keep their
+// edge-list order and ties between nodes are broken by original id.
+#include "asnn_common.h"
+
+namespace asnn {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+__device__ inline void flag_error(int *err, int code) { atomicCAS(err, 0, code); }
+
+__global__ void indegree_kernel(const int32_t *__restrict__ src, const int32_t *__restrict__ dst,
+                                const int32_t *__restrict__ level, int64_t n_edges, int32_t n_nodes, int32_t n_levels,
+                                int32_t *indeg, int *err) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n_edges; e += stride) {
+        const int32_t a = src[e], b = dst[e];
+        if (a < 0 || a >= n_nodes || b < 0 || b >= n_nodes) { flag_error(err, ASNN_ERR_INDEX); continue; }
+        const int32_t la = level[a], lb = level[b];
+        if (la < 0 || la >= n_levels || lb < 0 || lb >= n_levels) { flag_error(err, ASNN_ERR_INDEX); continue; }
+        if (la >= lb) flag_error(err, ASNN_ERR_LEVEL_ORDER);
+        atomicAdd(&indeg[b], 1);
+    }
+}
+
+// key = 2*level + (0 if heavy else 1): heavy nodes lead their level.
+__global__ void node_key_kernel(const int32_t *__restrict__ level, const int32_t *__restrict__ indeg, int32_t n_nodes,
+                                int32_t n_levels, uint32_t *__restrict__ keys, uint32_t *__restrict__ vals, int *err) {
+    const int v = blockIdx.x * blockDim.x + threadIdx.x;
+    if (v >= n_nodes) return;
+    int32_t l = level[v];
+    if (l < 0 || l >= n_levels) { flag_error(err, ASNN_ERR_INDEX); l = 0; }
+    keys[v] = 2u * (uint32_t)l + (indeg[v] >= ASNN_HEAVY_INDEGREE ? 0u : 1u);
+    vals[v] = (uint32_t)v;
+}
+
+// perm = sorted node ids; inv_perm its inverse; packed_deg[i] = indeg[perm[i]].
+__global__ void permutation_kernel(const uint32_t *__restrict__ sorted_ids, const int32_t *__restrict__ indeg,
+                                   int32_t n_nodes, int32_t *__restrict__ perm, int32_t *__restrict__ inv_perm,
+                                   int32_t *__restrict__ packed_deg) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i > n_nodes) return;
+    if (i == n_nodes) { packed_deg[i] = 0; return; }
+    const int32_t v = (int32_t)sorted_ids[i];
+    perm[i] = v;
+    inv_perm[v] = i;
+    packed_deg[i] = indeg[v];
+}
+
+// level_ptr[k] = number of nodes whose key is < k  (k = 0 .. 2*n_levels).
+__global__ void level_ptr_kernel(const uint32_t *__restrict__ sorted_keys, int32_t n_nodes, int32_t n_keys,
+                                 int32_t *__restrict__ level_ptr) {
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k > n_keys) return;
+    int lo = 0, hi = n_nodes;
+    while (lo < hi) {
+        const int mid = lo + (hi - lo) / 2;
+        if (sorted_keys[mid] < (uint32_t)k) lo = mid + 1; else hi = mid;
+    }
+    level_ptr[k] = lo;
+}
+
+__global__ void edge_key_kernel(const int32_t *__restrict__ dst, const int32_t *__restrict__ inv_perm, int64_t n_edges,
+                                int32_t n_nodes, uint32_t *__restrict__ keys, uint32_t *__restrict__ vals) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n_edges; e += stride) {
+        const int32_t b = dst[e];
+        keys[e] = (b >= 0 && b < n_nodes) ? (uint32_t)inv_perm[b] : 0u;
+        vals[e] = (uint32_t)e;
+    }
+}
+
+__global__ void gather_edges_kernel(const uint32_t *__restrict__ sorted_edge, const int32_t *__restrict__ src,
+                                    const float *__restrict__ w, const int32_t *__restrict__ inv_perm, int64_t n_edges,
+                                    int32_t n_nodes, int32_t *__restrict__ col, float *__restrict__ w_packed) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < n_edges; j += stride) {
+        const uint32_t e = sorted_edge[j];
+        const int32_t a = src[e];
+        col[j] = (a >= 0 && a < n_nodes) ? inv_perm[a] : 0;
+        w_packed[j] = w[e];
+    }
+}
+
+}  // namespace
+
+struct PackWorkspace {
+    int *err;
+    int32_t *indeg, *packed_deg, *tmp;
+    uint32_t *keys_a, *vals_a, *keys_b, *vals_b;
+    size_t bytes;
+};
+
+static PackWorkspace carve_pack(void *ws, int32_t n_nodes, int64_t n_edges) {
+    Carver c(ws);
+    PackWorkspace w;
+    const size_t n = (size_t)n_nodes, e = (size_t)n_edges;
+    const size_t m = (n > e ? n : e) + 1;
+    w.err = c.take<int>(64);
+    w.indeg = c.take<int32_t>(n + 1);
+    w.packed_deg = c.take<int32_t>(n + 1);
+    w.keys_a = c.take<uint32_t>(m);
+    w.vals_a = c.take<uint32_t>(m);
+    w.keys_b = c.take<uint32_t>(m);
+    w.vals_b = c.take<uint32_t>(m);
+    const size_t t1 = radix_tmp_ints(m), t2 = scan_tmp_ints(n + 1);
+    w.tmp = c.take<int32_t>(t1 > t2 ? t1 : t2);
+    w.bytes = c.off;
+    return w;
+}
+
+}  // namespace asnn
+
+using namespace asnn;
+
+extern "C" size_t asnn_pack_workspace_bytes(int32_t n_nodes, int64_t n_edges) {
+    if (n_nodes < 0 || n_edges < 0) return 0;
+    return carve_pack(nullptr, n_nodes, n_edges).bytes;
+}
+
+extern "C" int asnn_pack_csr(int32_t n_nodes, int64_t n_edges, int32_t n_levels, const int32_t *src, const int32_t *dst,
+                             const float *w, const int32_t *level, int32_t *level_ptr, int32_t *level_ptr_host,
+                             int32_t *perm, int32_t *inv_perm, int32_t *row_ptr, int32_t *col, float *w_packed,
+                             void *workspace, size_t workspace_bytes, void *stream) {
+    if (n_nodes <= 0 || n_edges < 0 || n_edges >= (int64_t)INT32_MAX || n_levels <= 0 ||
+        n_levels > n_nodes || n_levels >= (1 << 30))
+        return ASNN_ERR_SIZE;
+    if (!level || !level_ptr || !level_ptr_host || !perm || !inv_perm || !row_ptr || !workspace) return ASNN_ERR_NULL;
+    if (n_edges > 0 && (!src || !dst || !w || !col || !w_packed)) return ASNN_ERR_NULL;
+    if (((uintptr_t)workspace & 255u) != 0 || workspace_bytes < asnn_pack_workspace_bytes(n_nodes, n_edges))
+        return ASNN_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    PackWorkspace ws = carve_pack(workspace, n_nodes, n_edges);
+    const size_t n = (size_t)n_nodes;
+    const int32_t n_keys = 2 * n_levels;
+
+    ASNN_HIP_TRY(hipMemsetAsync(ws.err, 0, (size_t)((char *)ws.packed_deg - (char *)ws.err), s));   // err + indeg
+    if (n_edges > 0) {
+        hipLaunchKernelGGL(indegree_kernel, dim3(blocks_for((size_t)n_edges, kThreads, 65535)), dim3(kThreads), 0, s,
+                           src, dst, level, n_edges, n_nodes, n_levels, ws.indeg, ws.err);
+        ASNN_HIP_TRY(hipGetLastError());
+    }
+    // nodes: stable sort by (level, heavy-first) key
+    hipLaunchKernelGGL(node_key_kernel, dim3(blocks_for(n, kThreads)), dim3(kThreads), 0, s, level,
+                       (const int32_t *)ws.indeg, n_nodes, n_levels, ws.keys_a, ws.vals_a, ws.err);
+    ASNN_HIP_TRY(hipGetLastError());
+    uint32_t *ks, *vs;
+    ASNN_TRY(radix_sort_pairs_u32(ws.keys_a, ws.vals_a, ws.keys_b, ws.vals_b, n, bits_for((uint64_t)n_keys), ws.tmp, s,
+                                  &ks, &vs));
+    hipLaunchKernelGGL(permutation_kernel, dim3(blocks_for(n + 1, kThreads)), dim3(kThreads), 0, s,
+                       (const uint32_t *)vs, (const int32_t *)ws.indeg, n_nodes, perm, inv_perm, ws.packed_deg);
+    ASNN_HIP_TRY(hipGetLastError());
+    hipLaunchKernelGGL(level_ptr_kernel, dim3(blocks_for((size_t)n_keys + 1, kThreads)), dim3(kThreads), 0, s,
+                       (const uint32_t *)ks, n_nodes, n_keys, level_ptr);
+    ASNN_HIP_TRY(hipGetLastError());
+    ASNN_TRY(exclusive_scan_i32(ws.packed_deg, row_ptr, n + 1, ws.tmp, s));
+
+    // edges: stable sort by packed destination keeps each node's edge-list order
+    if (n_edges > 0) {
+        const unsigned eb = blocks_for((size_t)n_edges, kThreads, 65535);
+        hipLaunchKernelGGL(edge_key_kernel, dim3(eb), dim3(kThreads), 0, s, dst, (const int32_t *)inv_perm, n_edges,
+                           n_nodes, ws.keys_a, ws.vals_a);
+        ASNN_HIP_TRY(hipGetLastError());
+        ASNN_TRY(radix_sort_pairs_u32(ws.keys_a, ws.vals_a, ws.keys_b, ws.vals_b, (size_t)n_edges,
+                                      bits_for((uint64_t)n_nodes - 1), ws.tmp, s, &ks, &vs));
+        hipLaunchKernelGGL(gather_edges_kernel, dim3(eb), dim3(kThreads), 0, s, (const uint32_t *)vs, src, w,
+                           (const int32_t *)inv_perm, n_edges, n_nodes, col, w_packed);
+        ASNN_HIP_TRY(hipGetLastError());
+    }
+    int host_err = 0;
+    ASNN_HIP_TRY(hipMemcpyAsync(&host_err, ws.err, sizeof(int), hipMemcpyDeviceToHost, s));
+    ASNN_HIP_TRY(hipMemcpyAsync(level_ptr_host, level_ptr, sizeof(int32_t) * ((size_t)n_keys + 1),
+                                hipMemcpyDeviceToHost, s));
+    ASNN_HIP_TRY(hipStreamSynchronize(s));
+    return host_err;
+}

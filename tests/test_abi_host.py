@@ -1,0 +1,117 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the
+header declares, and rejects bad arguments before touching a device."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2005_04347_amd as amd
+    if not os.path.exists(amd.binding.LIB_PATH):
+        from paper_2005_04347_amd.build import build
+        build(verbose=False)
+    return amd.load()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "asnn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(asnn_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert {"asnn_build_levels", "asnn_pack_csr", "asnn_activate"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), name
+    import paper_2005_04347_amd.binding as b
+    assert sorted(b.EXPORTS) == names
+
+
+def test_error_strings(lib):
+    assert lib.asnn_strerror(0) == b"ok"
+    seen = set()
+    for code in range(-10, 0):
+        s = lib.asnn_strerror(code)
+        assert s and s != b"unknown error" and s not in seen
+        seen.add(s)
+    assert lib.asnn_strerror(-99) == b"unknown error"
+    assert lib.asnn_version() >= 1
+
+
+def test_header_constants_match_binding():
+    import paper_2005_04347_amd.binding as b
+    text = open(os.path.join(ROOT, "include", "asnn.h")).read()
+    for name, code in re.findall(r"#define (ASNN_ERR_[A-Z_]+) \((-\d+)\)", text):
+        assert b.ERR_NAMES[int(code)] == name
+    assert int(re.search(r"#define ASNN_HEAVY_INDEGREE (\d+)", text).group(1)) == b.HEAVY_INDEGREE
+    assert int(re.search(r"#define ASNN_FLAG_RAW_INPUTS (\d+)u", text).group(1)) == b.FLAG_RAW_INPUTS
+    assert int(re.search(r"#define ASNN_FLAG_ACC_F32 (\d+)u", text).group(1)) == b.FLAG_ACC_F32
+
+
+def test_workspace_sizes_grow_and_align(lib):
+    a = lib.asnn_levels_workspace_bytes(1000, 10000)
+    b = lib.asnn_levels_workspace_bytes(100000, 1090000)
+    assert 0 < a < b and a % 256 == 0 and b % 256 == 0
+    # out-adjacency + two frontiers + a few node arrays: linear in N and E
+    assert b < 16 * (100000 * 8 + 1090000)
+    p = lib.asnn_pack_workspace_bytes(100000, 1090000)
+    assert p % 256 == 0 and p > 4 * 4 * 1090000
+    assert lib.asnn_levels_workspace_bytes(-1, 5) == 0
+
+
+def test_argument_checks_need_no_device(lib):
+    nl = ctypes.c_int32(-7)
+    fake = ctypes.c_void_p(256)          # never dereferenced: every call below fails a host-side check first
+    i32 = ctypes.c_int32
+    assert lib.asnn_build_levels(-1, 0, None, None, None, 0, fake, ctypes.byref(nl), fake, 1 << 20, None) == -2
+    assert lib.asnn_build_levels(4, -1, None, None, None, 0, fake, ctypes.byref(nl), fake, 1 << 20, None) == -2
+    assert lib.asnn_build_levels(4, 2**31, fake, fake, None, 0, fake, ctypes.byref(nl), fake, 1 << 20, None) == -2
+    assert lib.asnn_build_levels(4, 2, None, fake, None, 0, fake, ctypes.byref(nl), fake, 1 << 20, None) == -1
+    assert lib.asnn_build_levels(4, 2, fake, fake, None, 1, fake, ctypes.byref(nl), fake, 1 << 20, None) == -1
+    assert lib.asnn_build_levels(4, 2, fake, fake, None, 0, fake, ctypes.byref(nl), None, 1 << 20, None) == -1
+    assert lib.asnn_build_levels(4, 2, fake, fake, None, 0, fake, ctypes.byref(nl), fake, 16, None) == -7
+    assert lib.asnn_build_levels(4, 2, fake, fake, None, 0, fake, ctypes.byref(nl), ctypes.c_void_p(264), 1 << 20, None) == -7
+    assert lib.asnn_build_levels(0, 0, None, None, None, 0, None, ctypes.byref(nl), None, 0, None) == 0 and nl.value == 0
+    lph = (i32 * 3)(0, 0, 4)
+    assert lib.asnn_pack_csr(0, 0, 1, None, None, None, fake, fake, lph, fake, fake, fake, None, None, fake, 1 << 20, None) == -2
+    assert lib.asnn_pack_csr(4, 0, 9, None, None, None, fake, fake, lph, fake, fake, fake, None, None, fake, 1 << 20, None) == -2
+    assert lib.asnn_pack_csr(4, 0, 1, None, None, None, None, fake, lph, fake, fake, fake, None, None, fake, 1 << 20, None) == -1
+    assert lib.asnn_pack_csr(4, 0, 1, None, None, None, fake, fake, lph, fake, fake, fake, None, None, fake, 8, None) == -7
+    # activate: sizes, NULLs, alignment of V, and a level table that does not cover the rows
+    args = lambda **k: [k.get("n", 4), 0, 1, k.get("lph", lph), fake, None, None, fake, fake, k.get("n_in", 1), None, 0,
+                        fake, k.get("B", 2), k.get("V", fake), None, 0, None]
+    assert lib.asnn_activate(*args(B=0)) == -2
+    assert lib.asnn_activate(*args(n=0)) == -2
+    assert lib.asnn_activate(*args(V=None)) == -1
+    assert lib.asnn_activate(*args(V=ctypes.c_void_p(260))) == -2
+    assert lib.asnn_activate(*args(lph=(i32 * 3)(0, 0, 3))) == -2
+    assert lib.asnn_activate(*args(lph=(i32 * 3)(0, 5, 4))) == -2
+    assert lib.asnn_activate(*args(lph=None)) == -1
+
+
+def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
+    import paper_2005_04347_amd.binding as b
+    monkeypatch.setattr(b, "_lib", None)
+    monkeypatch.setattr(b, "LIB_PATH", str(tmp_path / "missing.so"))
+    with pytest.raises(ImportError):
+        b.load()
+
+
+def test_product_never_imports_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2005_04347_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c")):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_2005_04347_amd" not in text and "libasnn.so" not in text, f
