@@ -93,6 +93,21 @@ def main():
     dev_ms = sorted(a.elapsed_time(b) for a, b in ev)
     dev_ms_med = dev_ms[len(dev_ms) // 2]
 
+    # yardstick: what a plain streaming copy sustains on this device (read + write bytes)
+    n_copy = 256 * 1024 * 1024
+    ca = torch.empty(n_copy, dtype=torch.float32, device=dev)
+    cb = torch.empty(n_copy, dtype=torch.float32, device=dev)
+    for _ in range(2):
+        amd.asnn_device_copy(cb, ca)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        amd.asnn_device_copy(cb, ca)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 5 * 2.0 * 4.0 * n_copy / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del ca, cb
+
     edge_samples = float(wl.n_edges) * B
     value = edge_samples / (wall_ms * 1e-3) / 1e9
     lp = net.graph.level_ptr_host
@@ -118,7 +133,8 @@ def main():
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
                      "kernel": "gather_level_kernel (all level launches of one activation)",
                      "algorithmic_bytes_per_step": alg_bytes, "device_ms_per_step_median": round(dev_ms_med, 4),
-                     "device_ms_per_step_min": round(dev_ms[0], 4)},
+                     "device_ms_per_step_min": round(dev_ms[0], 4),
+                     "device_copy_GBps": round(copy_gbps, 1), "frac_of_device_copy": round(achieved / copy_gbps, 4)},
     }
     if not args.no_cpu:
         import oracle

@@ -137,6 +137,14 @@ int asnn_activate(int32_t n_nodes, int64_t n_edges, int32_t n_levels,
                   const float *X, int32_t B, float *V, float *Y,
                   uint32_t flags, void *stream);
 
+/* ---- yardstick -----------------------------------------------------------
+ * Plain streaming device-to-device copy of `bytes` bytes (a multiple of 16,
+ * both pointers 16-byte aligned, buffers must not overlap).  Not part of the
+ * method: the benchmark uses it to measure the copy bandwidth of the device
+ * and to calibrate hardware byte counters against a kernel of known traffic
+ * (reads `bytes`, writes `bytes`).  Errors: NULL, SIZE, HIP.  Asynchronous. */
+int asnn_device_copy(void *dst, const void *src, size_t bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     PackedGraph,
     asnn_activate,
     asnn_build_levels,
+    asnn_device_copy,
     asnn_pack_csr,
     load,
 )

@@ -30,7 +30,7 @@ ERR_NAMES = {
 EXPORTS = [
     "asnn_strerror", "asnn_last_hip_error", "asnn_version",
     "asnn_levels_workspace_bytes", "asnn_build_levels",
-    "asnn_pack_workspace_bytes", "asnn_pack_csr", "asnn_activate",
+    "asnn_pack_workspace_bytes", "asnn_pack_csr", "asnn_activate", "asnn_device_copy",
 ]
 
 
@@ -72,6 +72,8 @@ def load() -> ctypes.CDLL:
     lib.asnn_pack_csr.argtypes = [i32, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.asnn_activate.restype = ctypes.c_int
     lib.asnn_activate.argtypes = [i32, i64, i32, vp, vp, vp, vp, vp, vp, i32, vp, i32, vp, i32, vp, vp, u32, vp]
+    lib.asnn_device_copy.restype = ctypes.c_int
+    lib.asnn_device_copy.argtypes = [vp, vp, sz, vp]
     _lib = lib
     return lib
 
@@ -180,6 +182,16 @@ def asnn_activate(g: PackedGraph, input_ids: torch.Tensor, X: torch.Tensor,
     if rc != 0:
         raise AsnnError(rc, "asnn_activate")
     return V, Y
+
+
+def asnn_device_copy(dst: torch.Tensor, src: torch.Tensor):
+    """Streaming copy src -> dst on the current stream (bandwidth yardstick)."""
+    lib = load()
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes
+    rc = lib.asnn_device_copy(ctypes.c_void_p(dst.data_ptr()), ctypes.c_void_p(src.data_ptr()), nbytes, _stream())
+    if rc != 0:
+        raise AsnnError(rc, "asnn_device_copy")
 
 
 class Network:

@@ -18,7 +18,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libasnn.so")
-SOURCES = ["api.hip", "prims.hip", "levels.hip", "pack.hip", "activate.hip"]
+SOURCES = ["api.hip", "prims.hip", "levels.hip", "pack.hip", "activate.hip", "util.hip"]
 
 HIPCC = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
 FLAGS = [
