@@ -11,7 +11,6 @@ timings of the level launches, and the CPU oracle timed on this host.
 from __future__ import annotations
 
 import argparse
-import ctypes
 import json
 import os
 import sys
@@ -24,7 +23,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E bandwidth
 
 
-def algorithmic_bytes(n_nodes, n_edges, n_inputs, B, level0_rows):
+def algorithmic_bytes(n_nodes, n_edges, n_inputs, B):
     """Gather model of one activation: every connection fetches one fp32 of
     its source per sample and its (col, w) pair once; every node value is
     written once; row_ptr is read once; the inputs are read once."""
@@ -33,6 +32,18 @@ def algorithmic_bytes(n_nodes, n_edges, n_inputs, B, level0_rows):
     csr = 8.0 * n_edges + 4.0 * n_nodes
     inputs = 4.0 * n_inputs * B
     return gather + store + csr + inputs
+
+
+def measured_traffic(config, flags):
+    """HBM bytes per level launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary of this
+    workload (counter runs cannot be made from inside this process); None when no summary covers it."""
+    path = os.path.join(ROOT, "profiles", f"gather_kernel_config{config}_hbm_traffic.md")
+    if flags != 0 or not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch:"):
+            return float(line.split(":")[1])
+    return None
 
 
 def main():
@@ -110,9 +121,10 @@ def main():
 
     edge_samples = float(wl.n_edges) * B
     value = edge_samples / (wall_ms * 1e-3) / 1e9
-    lp = net.graph.level_ptr_host
-    alg_bytes = algorithmic_bytes(wl.n_nodes, wl.n_edges, len(wl.input_ids), B, int(lp[2]))
+    alg_bytes = algorithmic_bytes(wl.n_nodes, wl.n_edges, len(wl.input_ids), B)
     achieved = alg_bytes / (dev_ms_med * 1e-3) / 1e9
+    launches = max(net.n_levels - 1, 1)          # one gather launch per level above the input level
+    traffic = measured_traffic(args.config, args.flags)
     out = {
         "metric": "G edge*samples/s for full ASNN activation",
         "value": round(value, 3),
@@ -130,17 +142,25 @@ def main():
                    "n_levels": net.n_levels, "batch": B, "n_nets": wl.n_nets, "flags": args.flags,
                    "preprocess_ms_first_call": round(prep_ms, 2)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
-                     "kernel": "gather_level_kernel (all level launches of one activation)",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "kernel": "gather_light_kernel / gather_mixed_kernel (one launch per level)",
+                     "launches_per_step": launches,
+                     "algorithmic_bytes_per_launch": alg_bytes / launches,
+                     "avg_launch_us": round(dev_ms_med * 1e3 / launches, 3),
                      "algorithmic_bytes_per_step": alg_bytes, "device_ms_per_step_median": round(dev_ms_med, 4),
                      "device_ms_per_step_min": round(dev_ms[0], 4),
                      "device_copy_GBps": round(copy_gbps, 1), "frac_of_device_copy": round(achieved / copy_gbps, 4)},
     }
     if not args.no_cpu:
         import oracle
-        cols = min(B, 64)
+        # calibrate on 8 columns, then time as many columns as fit in about 15 s (columns are independent)
+        probe = np.ascontiguousarray(wl.X[:, :min(B, 8)])
+        oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, probe[:, :1])     # warm-up / build
+        t0 = time.perf_counter()
+        oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, probe)
+        per_col = (time.perf_counter() - t0) / probe.shape[1]
+        cols = int(max(1, min(B, 15.0 / max(per_col, 1e-9))))
         Xs = np.ascontiguousarray(wl.X[:, :cols])
-        oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, Xs[:, :1])        # warm-up
         t0 = time.perf_counter()
         oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, Xs)
         cpu_s = time.perf_counter() - t0

@@ -61,9 +61,13 @@ extern "C" {
 #define ASNN_FLAG_ACC_F32 2u     /* accumulate and squash in fp32 (default: fp64 accumulate and
                                     fp64 sigmoid, rounded once to fp32 on store) */
 
-/* Nodes with at least this many incoming connections are "heavy": inside a
- * level the packed order lists them first (see asnn_pack_csr). */
-#define ASNN_HEAVY_INDEGREE 512
+/* In-degree classes.  Inside a level the packed order lists the heavy nodes
+ * (in-degree >= ASNN_HEAVY_INDEGREE) first, then the medium ones
+ * (>= ASNN_MEDIUM_INDEGREE), then the light ones (see asnn_pack_csr): the
+ * activation gives a heavy row 16 wavefronts, a medium row 4, a light row 1. */
+#define ASNN_HEAVY_INDEGREE 256
+#define ASNN_MEDIUM_INDEGREE 32
+#define ASNN_CLASSES 3
 
 const char *asnn_strerror(int code);
 int asnn_last_hip_error(void);
@@ -90,13 +94,14 @@ int asnn_build_levels(int32_t n_nodes, int64_t n_edges,
 /* ---- 2. pack -----------------------------------------------------------
  * Level-contiguous, destination-sorted CSR (replaces the paper's per-node
  * record with its inNodes / inWeights arrays and the array sorted by layer).
- * Packed order: by level; inside a level the heavy nodes (in-degree >=
- * ASNN_HEAVY_INDEGREE) first, then the rest; ties by original id.  The
- * connections of one node keep their edge-list order.
+ * Packed order: by level; inside a level by in-degree class (heavy, medium,
+ * light); ties by original id.  The connections of one node keep their
+ * edge-list order.
  *   level          device int32[n_nodes]      from asnn_build_levels
- *   level_ptr      device int32[2*n_levels+1] level l: heavy nodes are packed rows
- *                  [level_ptr[2l], level_ptr[2l+1]), the others [level_ptr[2l+1], level_ptr[2l+2])
- *   level_ptr_host host   int32[2*n_levels+1] the same numbers for the host
+ *   level_ptr      device int32[3*n_levels+1] level l: heavy nodes are packed rows
+ *                  [level_ptr[3l], level_ptr[3l+1]), medium [level_ptr[3l+1], level_ptr[3l+2]),
+ *                  light [level_ptr[3l+2], level_ptr[3l+3])
+ *   level_ptr_host host   int32[3*n_levels+1] the same numbers for the host
  *   perm           device int32[n_nodes]      packed row -> original id
  *   inv_perm       device int32[n_nodes]      original id -> packed row
  *   row_ptr        device int32[n_nodes+1]    connections of packed row i are [row_ptr[i], row_ptr[i+1])
@@ -118,7 +123,7 @@ int asnn_pack_csr(int32_t n_nodes, int64_t n_edges, int32_t n_levels,
  * disjoint union of networks: a population is activated by one call) for B
  * input vectors (activation kernel listing; the layer barrier there is the
  * boundary between two level launches here).
- *   level_ptr_host host  int32[2*n_levels+1]  from asnn_pack_csr
+ *   level_ptr_host host  int32[3*n_levels+1]  from asnn_pack_csr
  *   row_ptr, col, w_packed, inv_perm  device  from asnn_pack_csr
  *   input_ids   device int32[n_inputs]  original ids; X row k feeds input_ids[k]
  *   output_ids  device int32[n_outputs] original ids (may be NULL if Y is NULL)

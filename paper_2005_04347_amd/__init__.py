@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     FLAG_ACC_F32,
     FLAG_RAW_INPUTS,
     HEAVY_INDEGREE,
+    MEDIUM_INDEGREE,
     Network,
     PackedGraph,
     asnn_activate,

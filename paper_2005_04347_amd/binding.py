@@ -19,7 +19,9 @@ LIB_PATH = os.path.join(_HERE, "libasnn.so")
 
 FLAG_RAW_INPUTS = 1
 FLAG_ACC_F32 = 2
-HEAVY_INDEGREE = 512
+HEAVY_INDEGREE = 256
+MEDIUM_INDEGREE = 32
+CLASSES = 3
 
 ERR_NAMES = {
     -1: "ASNN_ERR_NULL", -2: "ASNN_ERR_SIZE", -3: "ASNN_ERR_INDEX", -4: "ASNN_ERR_INPUT_HAS_INEDGE",
@@ -125,8 +127,8 @@ class PackedGraph:
     n_nodes: int
     n_edges: int
     n_levels: int
-    level_ptr: torch.Tensor          # device int32 [2*n_levels+1]
-    level_ptr_host: np.ndarray       # host int32 [2*n_levels+1]
+    level_ptr: torch.Tensor          # device int32 [3*n_levels+1]
+    level_ptr_host: np.ndarray       # host int32 [3*n_levels+1]
     perm: torch.Tensor               # device int32 [n_nodes]  packed row -> original id
     inv_perm: torch.Tensor           # device int32 [n_nodes]  original id -> packed row
     row_ptr: torch.Tensor            # device int32 [n_nodes+1]
@@ -138,7 +140,7 @@ def asnn_pack_csr(n_nodes: int, n_levels: int, src, dst, w, level) -> PackedGrap
     lib = load()
     device = src.device
     n_edges = int(src.numel())
-    nk = 2 * n_levels + 1
+    nk = CLASSES * n_levels + 1
     level_ptr = torch.empty(nk, dtype=torch.int32, device=device)
     level_ptr_host = np.zeros(nk, dtype=np.int32)
     perm = torch.empty(n_nodes, dtype=torch.int32, device=device)

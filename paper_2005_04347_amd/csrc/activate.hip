@@ -8,9 +8,11 @@
 // source row's tile, and the connection's (col, w) pair is wave-uniform (it is
 // fetched once per wave through the scalar path and reused across the whole
 // tile).  For narrow batches the 64 lanes split into G groups that walk G
-// connections at a time and are folded with a fixed butterfly, so results do
-// not depend on timing.  The layer barrier is the boundary between two
-// launches on the stream.
+// connections at a time and are folded with a fixed butterfly.  Rows with many
+// connections are shared by 4 (medium) or 16 (heavy) wavefronts whose partial
+// sums meet in LDS in wave order.  Nothing depends on timing: the same inputs
+// give the same bits.  The layer barrier is the boundary between two launches
+// on the stream.
 //
 // Arithmetic: products and sums in ACC (double by default, float with
 // ASNN_FLAG_ACC_F32), sigmoid(x) = 1/(1+e^(-4.97x)) in ACC, one rounding to
@@ -21,10 +23,10 @@ namespace asnn {
 
 namespace {
 
-constexpr int kBlock = 256;                     // 4 wavefronts: 4 (row, tile) items per block
-constexpr int kWavesPerBlock = kBlock / kWave;
-constexpr int kHeavyBlock = 1024;               // 16 wavefronts share one heavy row's connections
-constexpr int kHeavyWaves = kHeavyBlock / kWave;
+constexpr int kMixedBlock = 1024;                    // 16 wavefronts
+constexpr int kMixedWaves = kMixedBlock / kWave;
+constexpr int kMediumWaves = 4;                      // wavefronts per medium row
+constexpr int kUnroll = 8;                           // row tiles in flight per wavefront
 
 template <int VEC> struct Vec;
 template <> struct Vec<1> { using type = float; };
@@ -130,19 +132,21 @@ __device__ inline void row_sum(const int32_t *__restrict__ col, const float *__r
     }
 }
 
-// One wavefront per (row, tile).  rows [row_begin, row_end) all belong to one
-// level, so every source row was written by an earlier launch.
+// Light rows: one single-wavefront block per (row, tile).  Rows
+// [row_begin, row_end) all belong to one level, so every source row was
+// written by an earlier launch.  One wave per block keeps the scheduling
+// granularity at a wavefront: a slot frees as soon as its row is done.
 template <int VEC, int LPG, typename ACC, int U>
-__global__ __launch_bounds__(kBlock) void gather_level_kernel(const int32_t *__restrict__ row_ptr,
+__global__ __launch_bounds__(kWave) void gather_light_kernel(const int32_t *__restrict__ row_ptr,
                                                                const int32_t *__restrict__ col,
                                                                const float *__restrict__ w, float *V, int B,
                                                                int row_begin, int row_end, int tiles_per_row) {
     constexpr int T = LPG * VEC;                 // batch columns per tile
-    const int wave = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * kWavesPerBlock + threadIdx.x / kWave));
-    const int row = row_begin + wave / tiles_per_row;
-    const int tile = wave % tiles_per_row;
+    const int item = blockIdx.x;
+    const int row = row_begin + item / tiles_per_row;
+    const int tile = item % tiles_per_row;
     if (row >= row_end) return;
-    const int lane = threadIdx.x & (kWave - 1);
+    const int lane = threadIdx.x;
     const int c = tile * T + (lane % LPG) * VEC;
     const bool active = c < B;
     const int e0 = row_ptr[row], e1 = row_ptr[row + 1];
@@ -156,43 +160,71 @@ __global__ __launch_bounds__(kBlock) void gather_level_kernel(const int32_t *__r
     }
 }
 
-// One 16-wave block per (heavy row, tile): the waves split the row's
-// connections into contiguous chunks, partial sums meet in LDS and are added
-// in wave order.
+// A level that holds heavy or medium rows: one launch of 16-wave blocks.
+// Blocks [0, heavy_items) take one heavy (row, tile) each, all 16 waves on it;
+// the next medium_blocks blocks take four medium (row, tile) items, 4 waves on
+// each; the remaining blocks take sixteen light items, one wave each.  The
+// waves of one item split its connections into contiguous chunks; partial sums
+// meet in LDS and are added in wave order.
 template <int VEC, int LPG, typename ACC, int U>
-__global__ __launch_bounds__(kHeavyBlock) void gather_heavy_kernel(const int32_t *__restrict__ row_ptr,
+__global__ __launch_bounds__(kMixedBlock) void gather_mixed_kernel(const int32_t *__restrict__ row_ptr,
                                                                     const int32_t *__restrict__ col,
                                                                     const float *__restrict__ w, float *V, int B,
-                                                                    int row_begin, int row_end, int tiles_per_row) {
+                                                                    int heavy_begin, int medium_begin, int light_begin,
+                                                                    int light_end, int tiles_per_row,
+                                                                    unsigned heavy_items, unsigned medium_blocks) {
     constexpr int T = LPG * VEC;
-    __shared__ ACC part[kHeavyWaves][LPG * VEC];
-    const int item = blockIdx.x;
-    const int row = row_begin + item / tiles_per_row;
-    const int tile = item % tiles_per_row;
-    if (row >= row_end) return;
+    __shared__ ACC part[kMixedWaves][LPG * VEC];
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
     const int lane = threadIdx.x & (kWave - 1);
-    const int c = tile * T + (lane % LPG) * VEC;
-    const bool active = c < B;
-    const int e0 = row_ptr[row], e1 = row_ptr[row + 1];
-    const int chunk = (e1 - e0 + kHeavyWaves - 1) / kHeavyWaves;
-    const int b0 = min(e0 + wave * chunk, e1), b1 = min(b0 + chunk, e1);
-    ACC acc[VEC];
-    row_sum<VEC, LPG, ACC, U>(col, w, V, B, b0, b1, active ? c : 0, acc);
-    if (lane < LPG) {
-#pragma unroll
-        for (int j = 0; j < VEC; ++j) part[wave][lane * VEC + j] = acc[j];
+    int share, row_begin, row_end;      // waves per item, row range of this block's class
+    long long item;
+    if (blockIdx.x < heavy_items) {
+        share = kMixedWaves; row_begin = heavy_begin; row_end = medium_begin;
+        item = blockIdx.x;
+    } else if (blockIdx.x < heavy_items + medium_blocks) {
+        share = kMediumWaves; row_begin = medium_begin; row_end = light_begin;
+        item = (long long)(blockIdx.x - heavy_items) * (kMixedWaves / kMediumWaves) + wave / kMediumWaves;
+    } else {
+        share = 1; row_begin = light_begin; row_end = light_end;
+        item = (long long)(blockIdx.x - heavy_items - medium_blocks) * kMixedWaves + wave;
     }
-    __syncthreads();
-    if (threadIdx.x < LPG && active) {
+    const long long row_ll = row_begin + item / tiles_per_row;
+    const bool valid = row_ll < row_end;          // wave-uniform; invalid waves still reach the barrier
+    const int row = valid ? (int)row_ll : row_begin;
+    const int tile = (int)(item % tiles_per_row);
+    const int c = tile * T + (lane % LPG) * VEC;
+    const bool active = valid && c < B;
+    const int slice = wave % share;               // which chunk of the row's connections
+    ACC acc[VEC];
+    if (valid) {
+        const int e0 = row_ptr[row], e1 = row_ptr[row + 1];
+        const int chunk = (e1 - e0 + share - 1) / share;
+        const int b0 = min(e0 + slice * chunk, e1), b1 = min(b0 + chunk, e1);
+        row_sum<VEC, LPG, ACC, U>(col, w, V, B, b0, b1, active ? c : 0, acc);
+    } else {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) acc[j] = ACC(0);
+    }
+    if (share > 1) {                               // block-uniform
+        if (lane < LPG) {
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) part[wave][lane * VEC + j] = acc[j];
+        }
+        __syncthreads();
+        if (slice == 0 && lane < LPG) {
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) {
+                ACC s = ACC(0);
+                for (int k = 0; k < share; ++k) s += part[wave + k][lane * VEC + j];
+                acc[j] = s;
+            }
+        }
+    }
+    if (active && slice == 0 && lane < LPG) {
         float out[VEC];
 #pragma unroll
-        for (int j = 0; j < VEC; ++j) {
-            ACC s = ACC(0);
-#pragma unroll
-            for (int k = 0; k < kHeavyWaves; ++k) s += part[k][threadIdx.x * VEC + j];
-            out[j] = squash(s);
-        }
+        for (int j = 0; j < VEC; ++j) out[j] = squash(acc[j]);
         store_vec<VEC>(V + (size_t)row * (size_t)B + c, out);
     }
 }
@@ -234,44 +266,52 @@ struct LevelArgs {
     hipStream_t s;
 };
 
+// One level: rows [hb, mb) heavy, [mb, lb) medium, [lb, le) light.
 template <int VEC, int LPG, typename ACC>
-int launch_rows(const LevelArgs &a, int heavy_begin, int light_begin, int light_end) {
-    constexpr int U = 8;
+int launch_level(const LevelArgs &a, int hb, int mb, int lb, int le) {
     const int vecs = a.B / VEC;
     const int tiles = (vecs + LPG - 1) / LPG;
-    if (light_begin > heavy_begin) {
-        const long long items = (long long)(light_begin - heavy_begin) * tiles;
-        hipLaunchKernelGGL((gather_heavy_kernel<VEC, LPG, ACC, U>), dim3((unsigned)items), dim3(kHeavyBlock), 0, a.s,
-                           a.row_ptr, a.col, a.w, a.V, a.B, heavy_begin, light_begin, tiles);
+    if (le <= hb) return ASNN_OK;
+    if (lb == hb) {      // light rows only
+        const long long items = (long long)(le - lb) * tiles;
+        if (items > 0x7fffffffLL) return ASNN_ERR_SIZE;
+        hipLaunchKernelGGL((gather_light_kernel<VEC, LPG, ACC, kUnroll>), dim3((unsigned)items), dim3(kWave), 0, a.s,
+                           a.row_ptr, a.col, a.w, a.V, a.B, lb, le, tiles);
         ASNN_HIP_TRY(hipGetLastError());
+        return ASNN_OK;
     }
-    if (light_end > light_begin) {
-        const long long items = (long long)(light_end - light_begin) * tiles;
-        const unsigned blocks = (unsigned)((items + kWavesPerBlock - 1) / kWavesPerBlock);
-        hipLaunchKernelGGL((gather_level_kernel<VEC, LPG, ACC, U>), dim3(blocks), dim3(kBlock), 0, a.s, a.row_ptr,
-                           a.col, a.w, a.V, a.B, light_begin, light_end, tiles);
-        ASNN_HIP_TRY(hipGetLastError());
-    }
+    const long long heavy_items = (long long)(mb - hb) * tiles;
+    const long long medium_items = (long long)(lb - mb) * tiles;
+    const long long light_items = (long long)(le - lb) * tiles;
+    const int per_block = kMixedWaves / kMediumWaves;
+    const long long medium_blocks = (medium_items + per_block - 1) / per_block;
+    const long long light_blocks = (light_items + kMixedWaves - 1) / kMixedWaves;
+    const long long blocks = heavy_items + medium_blocks + light_blocks;
+    if (blocks > 0x7fffffffLL) return ASNN_ERR_SIZE;
+    hipLaunchKernelGGL((gather_mixed_kernel<VEC, LPG, ACC, kUnroll>), dim3((unsigned)blocks), dim3(kMixedBlock), 0, a.s,
+                       a.row_ptr, a.col, a.w, a.V, a.B, hb, mb, lb, le, tiles, (unsigned)heavy_items,
+                       (unsigned)medium_blocks);
+    ASNN_HIP_TRY(hipGetLastError());
     return ASNN_OK;
 }
 
 template <int VEC, typename ACC>
-int launch_rows_vec(const LevelArgs &a, int hb, int lb, int le) {
+int launch_level_vec(const LevelArgs &a, int hb, int mb, int lb, int le) {
     const int vecs = a.B / VEC;
-    if (vecs > 32) return launch_rows<VEC, 64, ACC>(a, hb, lb, le);
-    if (vecs > 16) return launch_rows<VEC, 32, ACC>(a, hb, lb, le);
-    if (vecs > 8) return launch_rows<VEC, 16, ACC>(a, hb, lb, le);
-    if (vecs > 4) return launch_rows<VEC, 8, ACC>(a, hb, lb, le);
-    if (vecs > 2) return launch_rows<VEC, 4, ACC>(a, hb, lb, le);
-    if (vecs > 1) return launch_rows<VEC, 2, ACC>(a, hb, lb, le);
-    return launch_rows<VEC, 1, ACC>(a, hb, lb, le);
+    if (vecs > 32) return launch_level<VEC, 64, ACC>(a, hb, mb, lb, le);
+    if (vecs > 16) return launch_level<VEC, 32, ACC>(a, hb, mb, lb, le);
+    if (vecs > 8) return launch_level<VEC, 16, ACC>(a, hb, mb, lb, le);
+    if (vecs > 4) return launch_level<VEC, 8, ACC>(a, hb, mb, lb, le);
+    if (vecs > 2) return launch_level<VEC, 4, ACC>(a, hb, mb, lb, le);
+    if (vecs > 1) return launch_level<VEC, 2, ACC>(a, hb, mb, lb, le);
+    return launch_level<VEC, 1, ACC>(a, hb, mb, lb, le);
 }
 
 template <typename ACC>
-int launch_rows_any(const LevelArgs &a, int hb, int lb, int le) {
-    if (a.B % 4 == 0) return launch_rows_vec<4, ACC>(a, hb, lb, le);
-    if (a.B % 2 == 0) return launch_rows_vec<2, ACC>(a, hb, lb, le);
-    return launch_rows_vec<1, ACC>(a, hb, lb, le);
+int launch_level_any(const LevelArgs &a, int hb, int mb, int lb, int le) {
+    if (a.B % 4 == 0) return launch_level_vec<4, ACC>(a, hb, mb, lb, le);
+    if (a.B % 2 == 0) return launch_level_vec<2, ACC>(a, hb, mb, lb, le);
+    return launch_level_vec<1, ACC>(a, hb, mb, lb, le);
 }
 
 }  // namespace
@@ -294,8 +334,9 @@ extern "C" int asnn_activate(int32_t n_nodes, int64_t n_edges, int32_t n_levels,
     if (Y && n_outputs > 0 && !output_ids) return ASNN_ERR_NULL;
     if (((uintptr_t)V & 15u) != 0) return ASNN_ERR_SIZE;
     // the level table must be a monotone cover of the rows
-    if (level_ptr_host[0] != 0 || level_ptr_host[2 * n_levels] != n_nodes) return ASNN_ERR_SIZE;
-    for (int k = 0; k < 2 * n_levels; ++k)
+    const int n_keys = ASNN_CLASSES * n_levels;
+    if (level_ptr_host[0] != 0 || level_ptr_host[n_keys] != n_nodes) return ASNN_ERR_SIZE;
+    for (int k = 0; k < n_keys; ++k)
         if (level_ptr_host[k] > level_ptr_host[k + 1]) return ASNN_ERR_SIZE;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -304,11 +345,13 @@ extern "C" int asnn_activate(int32_t n_nodes, int64_t n_edges, int32_t n_levels,
     LevelArgs a{row_ptr, col, w_packed, V, B, s};
 
     for (int l = 0; l < n_levels; ++l) {
-        const int hb = level_ptr_host[2 * l], lb = level_ptr_host[2 * l + 1], le = level_ptr_host[2 * l + 2];
+        const int32_t *lp = level_ptr_host + ASNN_CLASSES * l;
+        const int hb = lp[0], mb = lp[1], lb = lp[2], le = lp[3];
         if (l == 0) {
             // Level 0 has no incoming connections.  Rows that are no sensors get
             // sigmoid(0); when every row of the level is a sensor the fill is skipped.
-            if (le - hb != n_inputs) ASNN_TRY(f32 ? launch_rows_any<float>(a, hb, lb, le) : launch_rows_any<double>(a, hb, lb, le));
+            if (le - hb != n_inputs)
+                ASNN_TRY(f32 ? launch_level_any<float>(a, hb, mb, lb, le) : launch_level_any<double>(a, hb, mb, lb, le));
             if (n_inputs > 0) {
                 const unsigned blocks = blocks_for((size_t)n_inputs * (size_t)B, 256, 8192);
                 if (f32)
@@ -321,7 +364,7 @@ extern "C" int asnn_activate(int32_t n_nodes, int64_t n_edges, int32_t n_levels,
             }
             continue;
         }
-        ASNN_TRY(f32 ? launch_rows_any<float>(a, hb, lb, le) : launch_rows_any<double>(a, hb, lb, le));
+        ASNN_TRY(f32 ? launch_level_any<float>(a, hb, mb, lb, le) : launch_level_any<double>(a, hb, mb, lb, le));
     }
     if (Y && n_outputs > 0) {
         const unsigned blocks = blocks_for((size_t)n_outputs * (size_t)B, 256, 8192);

@@ -36,14 +36,16 @@ __global__ void indegree_kernel(const int32_t *__restrict__ src, const int32_t *
     }
 }
 
-// key = 2*level + (0 if heavy else 1): heavy nodes lead their level.
+// key = 3*level + class (0 heavy, 1 medium, 2 light): heavier nodes lead their level.
 __global__ void node_key_kernel(const int32_t *__restrict__ level, const int32_t *__restrict__ indeg, int32_t n_nodes,
                                 int32_t n_levels, uint32_t *__restrict__ keys, uint32_t *__restrict__ vals, int *err) {
     const int v = blockIdx.x * blockDim.x + threadIdx.x;
     if (v >= n_nodes) return;
     int32_t l = level[v];
     if (l < 0 || l >= n_levels) { flag_error(err, ASNN_ERR_INDEX); l = 0; }
-    keys[v] = 2u * (uint32_t)l + (indeg[v] >= ASNN_HEAVY_INDEGREE ? 0u : 1u);
+    const int32_t d = indeg[v];
+    const uint32_t cls = d >= ASNN_HEAVY_INDEGREE ? 0u : (d >= ASNN_MEDIUM_INDEGREE ? 1u : 2u);
+    keys[v] = (uint32_t)ASNN_CLASSES * (uint32_t)l + cls;
     vals[v] = (uint32_t)v;
 }
 
@@ -60,7 +62,7 @@ __global__ void permutation_kernel(const uint32_t *__restrict__ sorted_ids, cons
     packed_deg[i] = indeg[v];
 }
 
-// level_ptr[k] = number of nodes whose key is < k  (k = 0 .. 2*n_levels).
+// level_ptr[k] = number of nodes whose key is < k  (k = 0 .. 3*n_levels).
 __global__ void level_ptr_kernel(const uint32_t *__restrict__ sorted_keys, int32_t n_nodes, int32_t n_keys,
                                  int32_t *__restrict__ level_ptr) {
     const int k = blockIdx.x * blockDim.x + threadIdx.x;
@@ -136,7 +138,7 @@ extern "C" int asnn_pack_csr(int32_t n_nodes, int64_t n_edges, int32_t n_levels,
                              int32_t *perm, int32_t *inv_perm, int32_t *row_ptr, int32_t *col, float *w_packed,
                              void *workspace, size_t workspace_bytes, void *stream) {
     if (n_nodes <= 0 || n_edges < 0 || n_edges >= (int64_t)INT32_MAX || n_levels <= 0 ||
-        n_levels > n_nodes || n_levels >= (1 << 30))
+        n_levels > n_nodes || n_levels >= (1 << 29))
         return ASNN_ERR_SIZE;
     if (!level || !level_ptr || !level_ptr_host || !perm || !inv_perm || !row_ptr || !workspace) return ASNN_ERR_NULL;
     if (n_edges > 0 && (!src || !dst || !w || !col || !w_packed)) return ASNN_ERR_NULL;
@@ -145,7 +147,7 @@ extern "C" int asnn_pack_csr(int32_t n_nodes, int64_t n_edges, int32_t n_levels,
     hipStream_t s = static_cast<hipStream_t>(stream);
     PackWorkspace ws = carve_pack(workspace, n_nodes, n_edges);
     const size_t n = (size_t)n_nodes;
-    const int32_t n_keys = 2 * n_levels;
+    const int32_t n_keys = ASNN_CLASSES * n_levels;
 
     ASNN_HIP_TRY(hipMemsetAsync(ws.err, 0, (size_t)((char *)ws.packed_deg - (char *)ws.err), s));   // err + indeg
     if (n_edges > 0) {
@@ -153,7 +155,7 @@ extern "C" int asnn_pack_csr(int32_t n_nodes, int64_t n_edges, int32_t n_levels,
                            src, dst, level, n_edges, n_nodes, n_levels, ws.indeg, ws.err);
         ASNN_HIP_TRY(hipGetLastError());
     }
-    // nodes: stable sort by (level, heavy-first) key
+    // nodes: stable sort by (level, in-degree class) key
     hipLaunchKernelGGL(node_key_kernel, dim3(blocks_for(n, kThreads)), dim3(kThreads), 0, s, level,
                        (const int32_t *)ws.indeg, n_nodes, n_levels, ws.keys_a, ws.vals_a, ws.err);
     ASNN_HIP_TRY(hipGetLastError());

@@ -51,6 +51,8 @@ def test_header_constants_match_binding():
     for name, code in re.findall(r"#define (ASNN_ERR_[A-Z_]+) \((-\d+)\)", text):
         assert b.ERR_NAMES[int(code)] == name
     assert int(re.search(r"#define ASNN_HEAVY_INDEGREE (\d+)", text).group(1)) == b.HEAVY_INDEGREE
+    assert int(re.search(r"#define ASNN_MEDIUM_INDEGREE (\d+)", text).group(1)) == b.MEDIUM_INDEGREE
+    assert int(re.search(r"#define ASNN_CLASSES (\d+)", text).group(1)) == b.CLASSES
     assert int(re.search(r"#define ASNN_FLAG_RAW_INPUTS (\d+)u", text).group(1)) == b.FLAG_RAW_INPUTS
     assert int(re.search(r"#define ASNN_FLAG_ACC_F32 (\d+)u", text).group(1)) == b.FLAG_ACC_F32
 
@@ -79,7 +81,7 @@ def test_argument_checks_need_no_device(lib):
     assert lib.asnn_build_levels(4, 2, fake, fake, None, 0, fake, ctypes.byref(nl), fake, 16, None) == -7
     assert lib.asnn_build_levels(4, 2, fake, fake, None, 0, fake, ctypes.byref(nl), ctypes.c_void_p(264), 1 << 20, None) == -7
     assert lib.asnn_build_levels(0, 0, None, None, None, 0, None, ctypes.byref(nl), None, 0, None) == 0 and nl.value == 0
-    lph = (i32 * 3)(0, 0, 4)
+    lph = (i32 * 4)(0, 0, 0, 4)
     assert lib.asnn_pack_csr(0, 0, 1, None, None, None, fake, fake, lph, fake, fake, fake, None, None, fake, 1 << 20, None) == -2
     assert lib.asnn_pack_csr(4, 0, 9, None, None, None, fake, fake, lph, fake, fake, fake, None, None, fake, 1 << 20, None) == -2
     assert lib.asnn_pack_csr(4, 0, 1, None, None, None, None, fake, lph, fake, fake, fake, None, None, fake, 1 << 20, None) == -1
@@ -91,8 +93,8 @@ def test_argument_checks_need_no_device(lib):
     assert lib.asnn_activate(*args(n=0)) == -2
     assert lib.asnn_activate(*args(V=None)) == -1
     assert lib.asnn_activate(*args(V=ctypes.c_void_p(260))) == -2
-    assert lib.asnn_activate(*args(lph=(i32 * 3)(0, 0, 3))) == -2
-    assert lib.asnn_activate(*args(lph=(i32 * 3)(0, 5, 4))) == -2
+    assert lib.asnn_activate(*args(lph=(i32 * 4)(0, 0, 0, 3))) == -2
+    assert lib.asnn_activate(*args(lph=(i32 * 4)(0, 5, 4, 4))) == -2
     assert lib.asnn_activate(*args(lph=None)) == -1
 
 

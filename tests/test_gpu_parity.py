@@ -31,15 +31,15 @@ def amd():
     return _amd()
 
 
-def expected_pack(wl, level, n_levels, heavy=512):
+def expected_pack(wl, level, n_levels, heavy=256, medium=32):
     """Host-side statement of what asnn_pack_csr must produce (numpy only)."""
     n = wl.n_nodes
     indeg = np.bincount(wl.dst, minlength=n)
-    key = 2 * level.astype(np.int64) + (indeg < heavy)
+    key = 3 * level.astype(np.int64) + np.where(indeg >= heavy, 0, np.where(indeg >= medium, 1, 2))
     perm = np.argsort(key, kind="stable").astype(np.int32)
     inv = np.empty(n, dtype=np.int32)
     inv[perm] = np.arange(n, dtype=np.int32)
-    level_ptr = np.searchsorted(key[perm], np.arange(2 * n_levels + 1), side="left").astype(np.int32)
+    level_ptr = np.searchsorted(key[perm], np.arange(3 * n_levels + 1), side="left").astype(np.int32)
     row_ptr = np.concatenate([[0], np.cumsum(indeg[perm])]).astype(np.int32)
     order = np.argsort(inv[wl.dst], kind="stable")
     col = inv[wl.src[order]]
@@ -110,12 +110,12 @@ def _heavy_workload(B, seed=3):
     """A few rows with in-degree far above the heavy threshold (parallel edges
     included), mixed with light rows and a non-sensor root."""
     rng = np.random.default_rng(seed)
-    n_in, n_mid = 300, 40
+    n_in, n_mid = 300, 60
     n = n_in + 1 + n_mid + 3
     root = n_in                      # zero in-degree, not a sensor
     src, dst = [], []
     for m in range(n_mid):
-        d = [1, 7, 511, 512, 513, 900, 4096, 5000][m % 8]
+        d = [1, 7, 31, 32, 33, 100, 255, 256, 257, 900, 4096, 5000][m % 12]
         src += rng.integers(0, n_in + 1, size=d).tolist()
         dst += [n_in + 1 + m] * d
     for t in range(3):
@@ -137,7 +137,8 @@ def test_heavy_rows_and_non_sensor_root(amd, B):
     wl, root = _heavy_workload(B)
     net, V, _ = run_gpu(amd, wl)
     lp = net.graph.level_ptr_host
-    assert lp[3] - lp[2] > 0 and lp[5] - lp[4] > 0          # heavy ranges are populated
+    assert lp[4] - lp[3] > 0 and lp[7] - lp[6] > 0          # heavy ranges of levels 1 and 2 are populated
+    assert lp[5] - lp[4] > 0 and lp[6] - lp[5] > 0          # and so are the medium and light ones of level 1
     want = oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.X)
     got = net.values_original_order(V).cpu().numpy()
     assert (got[root] == np.float32(0.5)).all()
