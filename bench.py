@@ -53,6 +53,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--flags", type=int, default=0, help="asnn_activate flags (2 = fp32 accumulate)")
+    ap.add_argument("--schedule", choices=["auto", "levels", "dataflow"], default="auto",
+                    help="level launches, persistent dataflow launch, or the library's own choice")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -79,8 +81,10 @@ def main():
     V = torch.empty((wl.n_nodes, B), dtype=torch.float32, device=dev)
     Y = torch.empty((len(wl.output_ids), B), dtype=torch.float32, device=dev)
 
+    flags = args.flags | {"auto": 0, "levels": amd.FLAG_LEVEL_LAUNCHES, "dataflow": amd.FLAG_DATAFLOW}[args.schedule]
+
     def step():
-        net.activate(X, V=V, Y=Y, flags=args.flags)
+        net.activate(X, V=V, Y=Y, flags=flags)
 
     for _ in range(args.warmup):
         step()
@@ -101,6 +105,7 @@ def main():
         step()
         b.record()
     torch.cuda.synchronize()
+    net.check(B)                                    # raises if a dataflow wait gave up
     dev_ms = sorted(a.elapsed_time(b) for a, b in ev)
     dev_ms_med = dev_ms[len(dev_ms) // 2]
 
@@ -139,7 +144,7 @@ def main():
         "dtype": "f32" if (args.flags & 2) else "f64",
         "data": "synthetic",
         "config": {"workload": f"config{args.config}:{wl.name}", "n_nodes": wl.n_nodes, "n_edges": wl.n_edges,
-                   "n_levels": net.n_levels, "batch": B, "n_nets": wl.n_nets, "flags": args.flags,
+                   "n_levels": net.n_levels, "batch": B, "n_nets": wl.n_nets, "flags": flags, "schedule": args.schedule,
                    "preprocess_ms_first_call": round(prep_ms, 2)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,

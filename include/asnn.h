@@ -55,11 +55,14 @@ extern "C" {
 #define ASNN_ERR_HIP (-8)                /* a HIP runtime call failed */
 #define ASNN_ERR_LEVEL_ORDER (-9)        /* level[] is not increasing along a connection */
 #define ASNN_ERR_NO_DEVICE (-10)         /* no HIP device available */
+#define ASNN_ERR_TIMEOUT (-11)           /* a dataflow wait exceeded its time limit */
 
 /* asnn_activate flags */
 #define ASNN_FLAG_RAW_INPUTS 1u  /* store sensor inputs unsquashed (the paper squashes them) */
 #define ASNN_FLAG_ACC_F32 2u     /* accumulate and squash in fp32 (default: fp64 accumulate and
                                     fp64 sigmoid, rounded once to fp32 on store) */
+#define ASNN_FLAG_LEVEL_LAUNCHES 4u  /* force one launch per level */
+#define ASNN_FLAG_DATAFLOW 8u        /* force the persistent dataflow launch (needs the workspace) */
 
 /* In-degree classes.  Inside a level the packed order lists the heavy nodes
  * (in-degree >= ASNN_HEAVY_INDEGREE) first, then the medium ones
@@ -97,50 +100,78 @@ int asnn_build_levels(int32_t n_nodes, int64_t n_edges,
  * Packed order: by level; inside a level by in-degree class (heavy, medium,
  * light); ties by original id.  The connections of one node keep their
  * edge-list order.
- *   level          device int32[n_nodes]      from asnn_build_levels
- *   level_ptr      device int32[3*n_levels+1] level l: heavy nodes are packed rows
- *                  [level_ptr[3l], level_ptr[3l+1]), medium [level_ptr[3l+1], level_ptr[3l+2]),
- *                  light [level_ptr[3l+2], level_ptr[3l+3])
- *   level_ptr_host host   int32[3*n_levels+1] the same numbers for the host
- *   perm           device int32[n_nodes]      packed row -> original id
- *   inv_perm       device int32[n_nodes]      original id -> packed row
- *   row_ptr        device int32[n_nodes+1]    connections of packed row i are [row_ptr[i], row_ptr[i+1])
- *   col            device int32[n_edges]      packed row of the connection's source
- *   w_packed       device float[n_edges]
- *   workspace      device, >= asnn_pack_workspace_bytes(), 256-byte aligned
+ *
+ * The packed network is described by an asnn_packed record.  The CALLER
+ * allocates every array it points to and fills the pointers (and n_nodes,
+ * n_edges, n_levels) before asnn_pack_csr; the call fills the arrays and the
+ * remaining scalars.  The record is plain data: the caller may copy it. */
+typedef struct asnn_packed {
+    int32_t n_nodes;
+    int32_t n_levels;
+    int64_t n_edges;
+    int32_t n_units;            /* out: number of work units (see unit_ptr) */
+    int32_t first_unit;         /* out: first unit above level 0 */
+    int32_t *level_ptr_host;    /* host   int32[3*n_levels+1]: copy of level_ptr for the host */
+    int32_t *level_ptr;         /* device int32[3*n_levels+1]: level l holds packed rows
+                                   [level_ptr[3l], level_ptr[3l+1]) heavy, [.. 3l+1, 3l+2) medium, [.. 3l+2, 3l+3) light */
+    int32_t *perm;              /* device int32[n_nodes]   packed row -> original id */
+    int32_t *inv_perm;          /* device int32[n_nodes]   original id -> packed row */
+    int32_t *row_ptr;           /* device int32[n_nodes+1] connections of packed row i are [row_ptr[i], row_ptr[i+1]) */
+    int32_t *col;               /* device int32[n_edges]   packed row of the connection's source */
+    float *w;                   /* device float[n_edges] */
+    int32_t *unit_ptr;          /* device int32[n_nodes+1] (n_units+1 used): unit u = packed rows
+                                   [unit_ptr[u], unit_ptr[u+1]), all of one level and class: 1 heavy row,
+                                   up to 4 medium rows or up to 16 light rows; units are in packed order */
+} asnn_packed;
+
+/*   src, dst, w  device            the connections, as for asnn_build_levels
+ *   level        device int32[n_nodes]  from asnn_build_levels
+ *   packed       host record, see above
+ *   workspace    device, >= asnn_pack_workspace_bytes(), 256-byte aligned
  * Errors: NULL, SIZE, INDEX (level outside [0,n_levels), id out of range),
- * LEVEL_ORDER, WORKSPACE, HIP.  Blocks until level_ptr_host is filled. */
+ * LEVEL_ORDER, WORKSPACE, HIP.  Blocks until the host fields are filled. */
 size_t asnn_pack_workspace_bytes(int32_t n_nodes, int64_t n_edges);
-int asnn_pack_csr(int32_t n_nodes, int64_t n_edges, int32_t n_levels,
-                  const int32_t *src, const int32_t *dst, const float *w, const int32_t *level,
-                  int32_t *level_ptr, int32_t *level_ptr_host,
-                  int32_t *perm, int32_t *inv_perm,
-                  int32_t *row_ptr, int32_t *col, float *w_packed,
-                  void *workspace, size_t workspace_bytes, void *stream);
+int asnn_pack_csr(const int32_t *src, const int32_t *dst, const float *w, const int32_t *level,
+                  asnn_packed *packed, void *workspace, size_t workspace_bytes, void *stream);
 
 /* ---- 3. activate -------------------------------------------------------
- * Level-synchronous full activation of the packed network (or of a packed
- * disjoint union of networks: a population is activated by one call) for B
- * input vectors (activation kernel listing; the layer barrier there is the
- * boundary between two level launches here).
- *   level_ptr_host host  int32[3*n_levels+1]  from asnn_pack_csr
- *   row_ptr, col, w_packed, inv_perm  device  from asnn_pack_csr
+ * Full activation of the packed network (or of a packed disjoint union of
+ * networks: a population is activated by one call) for B input vectors
+ * (activation kernel listing).  Two schedules compute the same bits:
+ *   - level launches: one launch per level on the stream; the boundary
+ *     between two launches is the paper's layer barrier;
+ *   - dataflow: one persistent launch; workgroups claim work units in packed
+ *     order and a row waits only for its own source rows (per-row ready
+ *     flags), so a deep, narrow network is not paced by a barrier per layer
+ *     (the paper names grid-wide synchronisation as future work).  Needs the
+ *     workspace and n_nodes*B*4 < 4 GiB.
+ * By default the dataflow schedule is taken when a workspace is given and the
+ * average level is small; ASNN_FLAG_LEVEL_LAUNCHES / ASNN_FLAG_DATAFLOW force one.
+ *   packed      host record filled by asnn_pack_csr
  *   input_ids   device int32[n_inputs]  original ids; X row k feeds input_ids[k]
+ *               (the ids given to asnn_build_levels)
  *   output_ids  device int32[n_outputs] original ids (may be NULL if Y is NULL)
  *   X           device float[n_inputs*B]
  *   V           device float[n_nodes*B]  receives the activation of EVERY node, packed
  *               row order (row i = node perm[i]); 16-byte aligned
  *   Y           device float[n_outputs*B] or NULL; receives the rows of output_ids
+ *   workspace   device, >= asnn_activate_workspace_bytes(n_nodes, B), 256-byte aligned,
+ *               or NULL (level launches only).  Contents need not be preserved.
  * Ids outside [0,n_nodes) in input_ids / output_ids are skipped (an output row
- * of such an id is filled with NaN).  Errors: NULL, SIZE, HIP.  Asynchronous. */
-int asnn_activate(int32_t n_nodes, int64_t n_edges, int32_t n_levels,
-                  const int32_t *level_ptr_host,
-                  const int32_t *row_ptr, const int32_t *col, const float *w_packed,
-                  const int32_t *inv_perm,
+ * of such an id is filled with NaN).  Errors: NULL, SIZE, WORKSPACE, HIP.
+ * Asynchronous.  A dataflow wait that exceeds its time limit (it cannot with
+ * a valid packed record) stops waiting and raises a flag in the workspace
+ * that asnn_activate_status reports. */
+size_t asnn_activate_workspace_bytes(int32_t n_nodes, int32_t B);
+int asnn_activate(const asnn_packed *packed,
                   const int32_t *input_ids, int32_t n_inputs,
                   const int32_t *output_ids, int32_t n_outputs,
                   const float *X, int32_t B, float *V, float *Y,
+                  void *workspace, size_t workspace_bytes,
                   uint32_t flags, void *stream);
+/* Synchronises the stream and returns ASNN_OK, or ASNN_ERR_TIMEOUT if the last
+ * dataflow activation that used this workspace gave up a wait.  NULL workspace: ASNN_OK. */
+int asnn_activate_status(const void *workspace, void *stream);
 
 /* ---- yardstick -----------------------------------------------------------
  * Plain streaming device-to-device copy of `bytes` bytes (a multiple of 16,

@@ -7,12 +7,16 @@ binding above it; build the library with ``python -m paper_2005_04347_amd.build`
 from .binding import (  # noqa: F401
     AsnnError,
     FLAG_ACC_F32,
+    FLAG_DATAFLOW,
+    FLAG_LEVEL_LAUNCHES,
     FLAG_RAW_INPUTS,
     HEAVY_INDEGREE,
     MEDIUM_INDEGREE,
     Network,
     PackedGraph,
     asnn_activate,
+    asnn_activate_status,
+    asnn_activate_workspace,
     asnn_build_levels,
     asnn_device_copy,
     asnn_pack_csr,

@@ -19,6 +19,8 @@ LIB_PATH = os.path.join(_HERE, "libasnn.so")
 
 FLAG_RAW_INPUTS = 1
 FLAG_ACC_F32 = 2
+FLAG_LEVEL_LAUNCHES = 4
+FLAG_DATAFLOW = 8
 HEAVY_INDEGREE = 256
 MEDIUM_INDEGREE = 32
 CLASSES = 3
@@ -26,13 +28,14 @@ CLASSES = 3
 ERR_NAMES = {
     -1: "ASNN_ERR_NULL", -2: "ASNN_ERR_SIZE", -3: "ASNN_ERR_INDEX", -4: "ASNN_ERR_INPUT_HAS_INEDGE",
     -5: "ASNN_ERR_DUP_INPUT", -6: "ASNN_ERR_CYCLE", -7: "ASNN_ERR_WORKSPACE", -8: "ASNN_ERR_HIP",
-    -9: "ASNN_ERR_LEVEL_ORDER", -10: "ASNN_ERR_NO_DEVICE",
+    -9: "ASNN_ERR_LEVEL_ORDER", -10: "ASNN_ERR_NO_DEVICE", -11: "ASNN_ERR_TIMEOUT",
 }
 
 EXPORTS = [
     "asnn_strerror", "asnn_last_hip_error", "asnn_version",
     "asnn_levels_workspace_bytes", "asnn_build_levels",
-    "asnn_pack_workspace_bytes", "asnn_pack_csr", "asnn_activate", "asnn_device_copy",
+    "asnn_pack_workspace_bytes", "asnn_pack_csr", "asnn_activate_workspace_bytes", "asnn_activate",
+    "asnn_activate_status", "asnn_device_copy",
 ]
 
 
@@ -71,9 +74,13 @@ def load() -> ctypes.CDLL:
     lib.asnn_pack_workspace_bytes.restype = sz
     lib.asnn_pack_workspace_bytes.argtypes = [i32, i64]
     lib.asnn_pack_csr.restype = ctypes.c_int
-    lib.asnn_pack_csr.argtypes = [i32, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.asnn_pack_csr.argtypes = [vp, vp, vp, vp, ctypes.POINTER(AsnnPacked), vp, sz, vp]
+    lib.asnn_activate_workspace_bytes.restype = sz
+    lib.asnn_activate_workspace_bytes.argtypes = [i32, i32]
     lib.asnn_activate.restype = ctypes.c_int
-    lib.asnn_activate.argtypes = [i32, i64, i32, vp, vp, vp, vp, vp, vp, i32, vp, i32, vp, i32, vp, vp, u32, vp]
+    lib.asnn_activate.argtypes = [ctypes.POINTER(AsnnPacked), vp, i32, vp, i32, vp, i32, vp, vp, vp, sz, u32, vp]
+    lib.asnn_activate_status.restype = ctypes.c_int
+    lib.asnn_activate_status.argtypes = [vp, vp]
     lib.asnn_device_copy.restype = ctypes.c_int
     lib.asnn_device_copy.argtypes = [vp, vp, sz, vp]
     _lib = lib
@@ -122,6 +129,17 @@ def asnn_build_levels(n_nodes: int, src: torch.Tensor, dst: torch.Tensor, input_
     return level[:n_nodes], int(n_levels.value)
 
 
+class AsnnPacked(ctypes.Structure):
+    """Mirror of `asnn_packed` in include/asnn.h."""
+    _fields_ = [
+        ("n_nodes", ctypes.c_int32), ("n_levels", ctypes.c_int32), ("n_edges", ctypes.c_int64),
+        ("n_units", ctypes.c_int32), ("first_unit", ctypes.c_int32),
+        ("level_ptr_host", ctypes.c_void_p), ("level_ptr", ctypes.c_void_p), ("perm", ctypes.c_void_p),
+        ("inv_perm", ctypes.c_void_p), ("row_ptr", ctypes.c_void_p), ("col", ctypes.c_void_p),
+        ("w", ctypes.c_void_p), ("unit_ptr", ctypes.c_void_p),
+    ]
+
+
 @dataclass
 class PackedGraph:
     n_nodes: int
@@ -134,6 +152,10 @@ class PackedGraph:
     row_ptr: torch.Tensor            # device int32 [n_nodes+1]
     col: torch.Tensor                # device int32 [n_edges]
     w: torch.Tensor                  # device float32 [n_edges]
+    unit_ptr: torch.Tensor           # device int32 [n_nodes+1], n_units+1 entries used
+    n_units: int = 0
+    first_unit: int = 0
+    record: Optional[AsnnPacked] = None   # the C record (points into the tensors above)
 
 
 def asnn_pack_csr(n_nodes: int, n_levels: int, src, dst, w, level) -> PackedGraph:
@@ -148,21 +170,29 @@ def asnn_pack_csr(n_nodes: int, n_levels: int, src, dst, w, level) -> PackedGrap
     row_ptr = torch.empty(n_nodes + 1, dtype=torch.int32, device=device)
     col = torch.empty(max(n_edges, 1), dtype=torch.int32, device=device)
     wp = torch.empty(max(n_edges, 1), dtype=torch.float32, device=device)
+    unit_ptr = torch.empty(n_nodes + 1, dtype=torch.int32, device=device)
     ws = _workspace(lib.asnn_pack_workspace_bytes(n_nodes, n_edges), device)
-    rc = lib.asnn_pack_csr(n_nodes, n_edges, n_levels, _ptr(src), _ptr(dst), _ptr(w), _ptr(level),
-                           ctypes.c_void_p(level_ptr.data_ptr()), level_ptr_host.ctypes.data_as(ctypes.c_void_p),
-                           ctypes.c_void_p(perm.data_ptr()), ctypes.c_void_p(inv_perm.data_ptr()),
-                           ctypes.c_void_p(row_ptr.data_ptr()), ctypes.c_void_p(col.data_ptr()),
-                           ctypes.c_void_p(wp.data_ptr()), ctypes.c_void_p(ws.data_ptr()), ws.numel(), _stream())
+    rec = AsnnPacked(n_nodes=n_nodes, n_levels=n_levels, n_edges=n_edges, n_units=0, first_unit=0,
+                     level_ptr_host=level_ptr_host.ctypes.data, level_ptr=level_ptr.data_ptr(), perm=perm.data_ptr(),
+                     inv_perm=inv_perm.data_ptr(), row_ptr=row_ptr.data_ptr(), col=col.data_ptr(), w=wp.data_ptr(),
+                     unit_ptr=unit_ptr.data_ptr())
+    rc = lib.asnn_pack_csr(_ptr(src), _ptr(dst), _ptr(w), _ptr(level), ctypes.byref(rec),
+                           ctypes.c_void_p(ws.data_ptr()), ws.numel(), _stream())
     if rc != 0:
         raise AsnnError(rc, "asnn_pack_csr")
     return PackedGraph(n_nodes, n_edges, n_levels, level_ptr, level_ptr_host, perm, inv_perm, row_ptr,
-                       col[:n_edges], wp[:n_edges])
+                       col[:n_edges], wp[:n_edges], unit_ptr, int(rec.n_units), int(rec.first_unit), rec)
+
+
+def asnn_activate_workspace(g: PackedGraph, B: int, device) -> torch.Tensor:
+    """Device scratch for the dataflow schedule of asnn_activate (contents need not be preserved)."""
+    lib = load()
+    return _workspace(lib.asnn_activate_workspace_bytes(g.n_nodes, B), device)
 
 
 def asnn_activate(g: PackedGraph, input_ids: torch.Tensor, X: torch.Tensor,
                   output_ids: Optional[torch.Tensor] = None, V: Optional[torch.Tensor] = None,
-                  Y: Optional[torch.Tensor] = None, flags: int = 0):
+                  Y: Optional[torch.Tensor] = None, flags: int = 0, workspace: Optional[torch.Tensor] = None):
     """Enqueues one full activation on the current stream.
     X: float32 [n_inputs, B].  Returns (V [n_nodes, B] in packed row order, Y [n_outputs, B] or None)."""
     lib = load()
@@ -177,13 +207,21 @@ def asnn_activate(g: PackedGraph, input_ids: torch.Tensor, X: torch.Tensor,
     n_out = 0 if output_ids is None else int(output_ids.numel())
     if output_ids is not None and Y is None:
         Y = torch.empty((n_out, B), dtype=torch.float32, device=device)
-    rc = lib.asnn_activate(g.n_nodes, g.n_edges, g.n_levels, g.level_ptr_host.ctypes.data_as(ctypes.c_void_p),
-                           _ptr(g.row_ptr), _ptr(g.col), _ptr(g.w), _ptr(g.inv_perm),
-                           _ptr(input_ids), n_in, _ptr(output_ids), n_out, _ptr(X), B,
-                           ctypes.c_void_p(V.data_ptr()), _ptr(Y), flags, _stream())
+    ws_ptr = None if workspace is None else ctypes.c_void_p(workspace.data_ptr())
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = lib.asnn_activate(ctypes.byref(g.record), _ptr(input_ids), n_in, _ptr(output_ids), n_out, _ptr(X), B,
+                           ctypes.c_void_p(V.data_ptr()), _ptr(Y), ws_ptr, ws_bytes, flags, _stream())
     if rc != 0:
         raise AsnnError(rc, "asnn_activate")
     return V, Y
+
+
+def asnn_activate_status(workspace: Optional[torch.Tensor]) -> None:
+    """Synchronises the current stream; raises if a dataflow wait of the last activation gave up."""
+    lib = load()
+    rc = lib.asnn_activate_status(None if workspace is None else ctypes.c_void_p(workspace.data_ptr()), _stream())
+    if rc != 0:
+        raise AsnnError(rc, "asnn_activate_status")
 
 
 def asnn_device_copy(dst: torch.Tensor, src: torch.Tensor):
@@ -211,10 +249,23 @@ class Network:
             self.level, self.n_levels = asnn_build_levels(self.n_nodes, self.src, self.dst, self.input_ids)
             self.graph = asnn_pack_csr(self.n_nodes, self.n_levels, self.src, self.dst, self.w_edges, self.level)
 
-    def activate(self, X, V=None, Y=None, flags: int = 0):
+        self._workspaces = {}
+
+    def workspace(self, B: int) -> torch.Tensor:
+        if B not in self._workspaces:
+            self._workspaces[B] = asnn_activate_workspace(self.graph, B, self.device)
+        return self._workspaces[B]
+
+    def activate(self, X, V=None, Y=None, flags: int = 0, use_workspace: bool = True):
         X = _dev_f32(X, self.device)
         with torch.cuda.device(self.device):
-            return asnn_activate(self.graph, self.input_ids, X, self.output_ids, V=V, Y=Y, flags=flags)
+            ws = self.workspace(int(X.shape[1])) if use_workspace else None
+            return asnn_activate(self.graph, self.input_ids, X, self.output_ids, V=V, Y=Y, flags=flags, workspace=ws)
+
+    def check(self, B: int) -> None:
+        """Synchronises and raises if the last dataflow activation at batch B timed out."""
+        with torch.cuda.device(self.device):
+            asnn_activate_status(self._workspaces.get(B))
 
     def values_original_order(self, V: torch.Tensor) -> torch.Tensor:
         """V (packed rows) -> [n_nodes, B] indexed by original node id (plain torch indexing, for tests)."""

@@ -229,6 +229,228 @@ __global__ __launch_bounds__(kMixedBlock) void gather_mixed_kernel(const int32_t
     }
 }
 
+
+// ---------------------------------------------------------------- dataflow
+// One persistent launch instead of one launch per level.  Workgroups claim
+// work items (unit, tile) in packed order from a global counter.  A row's
+// wavefront first polls the ready flags of its own source rows, then gathers;
+// when it has stored its tile it raises the row's flag.  An item only waits
+// for items with a smaller index, and an item is claimed by a running
+// workgroup after every smaller item was claimed, so the smallest unfinished
+// item never waits for anything: no deadlock for any grid size.
+//
+// Cross-workgroup visibility without cache flushes: V tiles and flags are read
+// and written with device-scope (sc1) accesses, which bypass the per-XCD L2
+// for lines that another XCD may have written; the writer waits for its stores
+// to complete (vmcnt) before it raises the flag.
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
+typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
+constexpr int kAuxDeviceScope = 16;                 // cache-policy bit sc1
+constexpr int kBufferFlags = 0x27000;               // raw 32-bit buffer, gfx9 descriptor word 3
+constexpr long long kWaitTicks = 200000000LL;       // 2 s of the 100 MHz wall clock
+
+struct DataflowCtl {
+    int head;       // next work item
+    int error;      // raised when a wait gave up
+    int magic;      // kCtlMagic once a dataflow launch has reset this block (the workspace may arrive uninitialised)
+    int pad[61];
+};
+constexpr int kCtlMagic = 0x41534e4e;
+
+template <int VEC>
+__device__ inline void load_vec_device_scope(__amdgpu_buffer_rsrc_t r, uint32_t byte_off, float (&out)[VEC]) {
+    if constexpr (VEC == 4) { floatx4 v = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, kAuxDeviceScope)); out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w; }
+    if constexpr (VEC == 2) { floatx2 v = __builtin_bit_cast(floatx2, __builtin_amdgcn_raw_buffer_load_b64(r, byte_off, 0, kAuxDeviceScope)); out[0] = v.x; out[1] = v.y; }
+    if constexpr (VEC == 1) { out[0] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, byte_off, 0, kAuxDeviceScope)); }
+}
+
+template <int VEC>
+__device__ inline void store_vec_device_scope(__amdgpu_buffer_rsrc_t r, uint32_t byte_off, const float (&in)[VEC]) {
+    if constexpr (VEC == 4) { floatx4 v = {in[0], in[1], in[2], in[3]}; __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uintx4, v), r, byte_off, 0, kAuxDeviceScope); }
+    if constexpr (VEC == 2) { floatx2 v = {in[0], in[1]}; __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(uintx2, v), r, byte_off, 0, kAuxDeviceScope); }
+    if constexpr (VEC == 1) { __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, in[0]), r, byte_off, 0, kAuxDeviceScope); }
+}
+
+// Blocks until every lane's source row (src, meaningful where `mine`) has
+// raised its flag for this tile.  Gives up after kWaitTicks or when another
+// wave already gave up, so every wave leaves the kernel.
+__device__ inline void wait_for_sources(bool mine, int src, int first_row, int tiles, int tile, const int *ready,
+                                        DataflowCtl *ctl) {
+    bool pending = mine && src >= first_row;
+    if (__any(pending)) {
+        const long long t0 = wall_clock64();
+        int spins = 0;
+        for (;;) {
+            if (pending) {
+                const int f = __hip_atomic_load(&ready[(size_t)(src - first_row) * (size_t)tiles + tile], __ATOMIC_RELAXED,
+                                                __HIP_MEMORY_SCOPE_AGENT);
+                pending = (f == 0);
+            }
+            if (!__any(pending)) break;
+            __builtin_amdgcn_s_sleep(1);
+            if ((++spins & 127) == 0) {
+                const int err = __hip_atomic_load(&ctl->error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (err != 0 || wall_clock64() - t0 > kWaitTicks) {
+                    __hip_atomic_store(&ctl->error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    break;
+                }
+            }
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
+// row_sum with waiting: connections are taken 64 at a time (one per lane),
+// their sources awaited, then gathered with device-scope loads.
+template <int VEC, int LPG, typename ACC, int U>
+__device__ inline void row_sum_dataflow(const int32_t *__restrict__ col, const float *__restrict__ w,
+                                        __amdgpu_buffer_rsrc_t vres, int B, int e_begin, int e_end, int c0, int first_row,
+                                        int tiles, int tile, const int *ready, DataflowCtl *ctl, ACC (&acc)[VEC]) {
+    constexpr int G = kWave / LPG;
+    const int lane = threadIdx.x & (kWave - 1);
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) acc[j] = ACC(0);
+    for (int eb = e_begin; eb < e_end; eb += kWave) {
+        const int n = min(kWave, e_end - eb);
+        const int my = eb + min(lane, n - 1);
+        const int mc = col[my];
+        const float mw = (lane < n) ? w[my] : 0.0f;
+        wait_for_sources(lane < n, mc, first_row, tiles, tile, ready, ctl);
+        if constexpr (G == 1) {
+            for (int i = 0; i < n; i += U) {
+                float vals[U][VEC];
+                float ww[U];
+#pragma unroll
+                for (int k = 0; k < U; ++k) {
+                    const int idx = min(i + k, n - 1);
+                    const int ck = __builtin_amdgcn_readlane(mc, idx);
+                    ww[k] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, mw), idx));
+                    load_vec_device_scope<VEC>(vres, ((uint32_t)ck * (uint32_t)B + (uint32_t)c0) * 4u, vals[k]);
+                }
+#pragma unroll
+                for (int k = 0; k < U; ++k)
+                    if (i + k < n) {        // wave-uniform
+#pragma unroll
+                        for (int j = 0; j < VEC; ++j) acc[j] += (ACC)ww[k] * (ACC)vals[k][j];
+                    }
+            }
+        } else {
+            const int g = lane / LPG;
+            for (int i = 0; i < n; i += G * U) {
+                float vals[U][VEC];
+                float ww[U];
+                bool ok[U];
+#pragma unroll
+                for (int k = 0; k < U; ++k) {
+                    const int idx = i + k * G + g;
+                    ok[k] = idx < n;
+                    const int sel = min(idx, n - 1);
+                    const int ck = __shfl(mc, sel, kWave);
+                    ww[k] = __shfl(mw, sel, kWave);
+                    load_vec_device_scope<VEC>(vres, ((uint32_t)ck * (uint32_t)B + (uint32_t)c0) * 4u, vals[k]);
+                }
+#pragma unroll
+                for (int k = 0; k < U; ++k)
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) {
+                        const ACC t = acc[j] + (ACC)ww[k] * (ACC)vals[k][j];
+                        acc[j] = ok[k] ? t : acc[j];
+                    }
+            }
+        }
+    }
+    if constexpr (G > 1) {
+#pragma unroll
+        for (int off = LPG; off < kWave; off <<= 1)
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) acc[j] += __shfl_xor(acc[j], off, kWave);
+    }
+}
+
+__global__ void dataflow_reset_kernel(int *ready, size_t n_flags, DataflowCtl *ctl) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_flags; i += stride) ready[i] = 0;
+    if (blockIdx.x == 0 && threadIdx.x < 64) reinterpret_cast<int *>(ctl)[threadIdx.x] = (threadIdx.x == 2) ? kCtlMagic : 0;
+}
+
+template <int VEC, int LPG, typename ACC, int U>
+__global__ __launch_bounds__(kMixedBlock) void dataflow_kernel(const int32_t *__restrict__ row_ptr,
+                                                                const int32_t *__restrict__ col,
+                                                                const float *__restrict__ w, float *V, uint32_t v_bytes,
+                                                                int B, const int32_t *__restrict__ unit_ptr,
+                                                                int first_unit, int n_work, int tiles, int first_row,
+                                                                int *ready, DataflowCtl *ctl) {
+    constexpr int T = LPG * VEC;
+    __shared__ ACC part[kMixedWaves][LPG * VEC];
+    __shared__ int s_claim;
+    const __amdgpu_buffer_rsrc_t vres = __builtin_amdgcn_make_buffer_rsrc(V, 0, (int)v_bytes, kBufferFlags);
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
+    const int lane = threadIdx.x & (kWave - 1);
+    for (;;) {
+        if (threadIdx.x == 0)
+            s_claim = __hip_atomic_fetch_add(&ctl->head, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        const int q = s_claim;
+        __syncthreads();
+        if (q >= n_work) return;                      // block-uniform
+        const int u = first_unit + q / tiles;
+        const int tile = q % tiles;
+        const int r0 = unit_ptr[u], r1 = unit_ptr[u + 1];
+        const int d0 = row_ptr[r0 + 1] - row_ptr[r0];
+        const int share = d0 >= ASNN_HEAVY_INDEGREE ? kMixedWaves : (d0 >= ASNN_MEDIUM_INDEGREE ? kMediumWaves : 1);
+        const int row_try = r0 + wave / share;
+        const bool valid = row_try < r1;
+        const int row = valid ? row_try : r0;
+        const int slice = wave % share;
+        const int c = tile * T + (lane % LPG) * VEC;
+        const bool active = valid && c < B;
+        ACC acc[VEC];
+        if (valid) {
+            const int e0 = row_ptr[row], e1 = row_ptr[row + 1];
+            const int chunk = (e1 - e0 + share - 1) / share;
+            const int b0 = min(e0 + slice * chunk, e1), b1 = min(b0 + chunk, e1);
+            row_sum_dataflow<VEC, LPG, ACC, U>(col, w, vres, B, b0, b1, active ? c : 0, first_row, tiles, tile, ready,
+                                               ctl, acc);
+        } else {
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) acc[j] = ACC(0);
+        }
+        if (share > 1) {                               // block-uniform
+            if (lane < LPG) {
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) part[wave][lane * VEC + j] = acc[j];
+            }
+            __syncthreads();
+            if (slice == 0 && lane < LPG) {
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) {
+                    ACC s = ACC(0);
+                    for (int k = 0; k < share; ++k) s += part[wave + k][lane * VEC + j];
+                    acc[j] = s;
+                }
+            }
+        }
+        if (valid && slice == 0) {                     // wave-uniform
+            if (active && lane < LPG) {
+                float out[VEC];
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) out[j] = squash(acc[j]);
+                store_vec_device_scope<VEC>(vres, ((uint32_t)row * (uint32_t)B + (uint32_t)c) * 4u, out);
+            }
+            // The tile must have reached device-scope visibility before the flag does: wait
+            // until every outstanding vector-memory operation of this wave has completed
+            // (s_waitcnt vmcnt(0); expcnt and lgkmcnt fields left at "no wait").
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            if (lane == 0)
+                __hip_atomic_store(&ready[(size_t)(row - first_row) * (size_t)tiles + tile], 1, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
 // Sensors: V[row of input_ids[k]][b] = sigmoid(X[k][b]) (or X raw).
 template <typename ACC>
 __global__ void stage_inputs_kernel(const int32_t *__restrict__ input_ids, const int32_t *__restrict__ inv_perm,
@@ -314,22 +536,117 @@ int launch_level_any(const LevelArgs &a, int hb, int mb, int lb, int le) {
     return launch_level_vec<1, ACC>(a, hb, mb, lb, le);
 }
 
+
+struct DataflowArgs {
+    const int32_t *unit_ptr;
+    int first_unit, n_work, first_row;
+    uint32_t v_bytes;
+    int *ready;
+    DataflowCtl *ctl;
+    int cus;
+};
+
+template <int VEC, int LPG, typename ACC>
+int launch_dataflow(const LevelArgs &a, const DataflowArgs &d) {
+    const int vecs = a.B / VEC;
+    const int tiles = (vecs + LPG - 1) / LPG;
+    static int per_cu = 0;       // resident 16-wave blocks per CU for this instantiation
+    if (per_cu == 0) {
+        int n = 0;
+        ASNN_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dataflow_kernel<VEC, LPG, ACC, kUnroll>,
+                                                                  kMixedBlock, 0));
+        per_cu = n > 0 ? n : 1;
+    }
+    long long blocks = (long long)d.cus * per_cu;
+    if (blocks > d.n_work) blocks = d.n_work;
+    if (blocks < 1) return ASNN_OK;
+    hipLaunchKernelGGL((dataflow_kernel<VEC, LPG, ACC, kUnroll>), dim3((unsigned)blocks), dim3(kMixedBlock), 0, a.s,
+                       a.row_ptr, a.col, a.w, a.V, d.v_bytes, a.B, d.unit_ptr, d.first_unit, d.n_work, tiles, d.first_row,
+                       d.ready, d.ctl);
+    ASNN_HIP_TRY(hipGetLastError());
+    return ASNN_OK;
+}
+
+template <int VEC, typename ACC>
+int launch_dataflow_vec(const LevelArgs &a, const DataflowArgs &d) {
+    const int vecs = a.B / VEC;
+    if (vecs > 32) return launch_dataflow<VEC, 64, ACC>(a, d);
+    if (vecs > 16) return launch_dataflow<VEC, 32, ACC>(a, d);
+    if (vecs > 8) return launch_dataflow<VEC, 16, ACC>(a, d);
+    if (vecs > 4) return launch_dataflow<VEC, 8, ACC>(a, d);
+    if (vecs > 2) return launch_dataflow<VEC, 4, ACC>(a, d);
+    if (vecs > 1) return launch_dataflow<VEC, 2, ACC>(a, d);
+    return launch_dataflow<VEC, 1, ACC>(a, d);
+}
+
+template <typename ACC>
+int launch_dataflow_any(const LevelArgs &a, const DataflowArgs &d) {
+    if (a.B % 4 == 0) return launch_dataflow_vec<4, ACC>(a, d);
+    if (a.B % 2 == 0) return launch_dataflow_vec<2, ACC>(a, d);
+    return launch_dataflow_vec<1, ACC>(a, d);
+}
+
+// Batch columns per tile and tiles per row for a given B (the same choice the launchers make).
+inline int tiles_for(int B) {
+    const int vec = (B % 4 == 0) ? 4 : (B % 2 == 0 ? 2 : 1);
+    const int vecs = B / vec;
+    int lpg = 1;
+    while (lpg < 64 && lpg < vecs) lpg <<= 1;
+    return (vecs + lpg - 1) / lpg;
+}
+
+struct ActivateWorkspace {
+    DataflowCtl *ctl;
+    int *ready;
+    size_t n_flags, bytes;
+};
+
+inline ActivateWorkspace carve_activate(void *ws, int32_t n_nodes, int32_t B) {
+    Carver c(ws);
+    ActivateWorkspace w;
+    w.ctl = c.take<DataflowCtl>(1);
+    w.n_flags = (size_t)n_nodes * (size_t)tiles_for(B);
+    w.ready = c.take<int>(w.n_flags + 1);
+    w.bytes = c.off;
+    return w;
+}
+
+// Average connections*samples per level below which the persistent dataflow
+// launch beats one launch per level (measured on MI355X: a level launch costs
+// about 8 us however little it does).
+constexpr double kDataflowMaxLevelWork = 8.0e6;
+
 }  // namespace
 }  // namespace asnn
 
 using namespace asnn;
 
-extern "C" int asnn_activate(int32_t n_nodes, int64_t n_edges, int32_t n_levels, const int32_t *level_ptr_host,
-                             const int32_t *row_ptr, const int32_t *col, const float *w_packed,
-                             const int32_t *inv_perm, const int32_t *input_ids, int32_t n_inputs,
+extern "C" size_t asnn_activate_workspace_bytes(int32_t n_nodes, int32_t B) {
+    if (n_nodes <= 0 || B <= 0) return 0;
+    return carve_activate(nullptr, n_nodes, B).bytes;
+}
+
+extern "C" int asnn_activate_status(const void *workspace, void *stream) {
+    ASNN_HIP_TRY(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+    if (!workspace) return ASNN_OK;
+    DataflowCtl host;
+    ASNN_HIP_TRY(hipMemcpy(&host, workspace, sizeof(host), hipMemcpyDeviceToHost));
+    return (host.magic == kCtlMagic && host.error) ? ASNN_ERR_TIMEOUT : ASNN_OK;
+}
+
+extern "C" int asnn_activate(const asnn_packed *packed, const int32_t *input_ids, int32_t n_inputs,
                              const int32_t *output_ids, int32_t n_outputs, const float *X, int32_t B, float *V,
-                             float *Y, uint32_t flags, void *stream) {
+                             float *Y, void *workspace, size_t workspace_bytes, uint32_t flags, void *stream) {
+    if (!packed) return ASNN_ERR_NULL;
+    const int32_t n_nodes = packed->n_nodes, n_levels = packed->n_levels;
+    const int64_t n_edges = packed->n_edges;
+    const int32_t *level_ptr_host = packed->level_ptr_host;
     if (n_nodes <= 0 || n_edges < 0 || n_edges >= (int64_t)INT32_MAX || n_levels <= 0 || n_inputs < 0 ||
         n_outputs < 0 || B <= 0)
         return ASNN_ERR_SIZE;
     if ((int64_t)n_nodes * (int64_t)B >= ((int64_t)1 << 40)) return ASNN_ERR_SIZE;
-    if (!level_ptr_host || !row_ptr || !inv_perm || !V) return ASNN_ERR_NULL;
-    if (n_edges > 0 && (!col || !w_packed)) return ASNN_ERR_NULL;
+    if (!level_ptr_host || !packed->row_ptr || !packed->inv_perm || !V) return ASNN_ERR_NULL;
+    if (n_edges > 0 && (!packed->col || !packed->w)) return ASNN_ERR_NULL;
     if (n_inputs > 0 && (!input_ids || !X)) return ASNN_ERR_NULL;
     if (Y && n_outputs > 0 && !output_ids) return ASNN_ERR_NULL;
     if (((uintptr_t)V & 15u) != 0) return ASNN_ERR_SIZE;
@@ -338,38 +655,77 @@ extern "C" int asnn_activate(int32_t n_nodes, int64_t n_edges, int32_t n_levels,
     if (level_ptr_host[0] != 0 || level_ptr_host[n_keys] != n_nodes) return ASNN_ERR_SIZE;
     for (int k = 0; k < n_keys; ++k)
         if (level_ptr_host[k] > level_ptr_host[k + 1]) return ASNN_ERR_SIZE;
+    if ((flags & ASNN_FLAG_LEVEL_LAUNCHES) && (flags & ASNN_FLAG_DATAFLOW)) return ASNN_ERR_SIZE;
+
+    // schedule
+    const int tiles = tiles_for(B);
+    const int first_row = n_levels > 1 ? level_ptr_host[ASNN_CLASSES] : n_nodes;
+    const long long n_work = (long long)(packed->n_units - packed->first_unit) * tiles;
+    const bool dataflow_possible = workspace && packed->unit_ptr && n_levels > 1 && packed->n_units > 0 &&
+                                   packed->first_unit >= 0 && packed->first_unit <= packed->n_units &&
+                                   packed->n_units <= n_nodes && n_work > 0 && n_work < 0x7fffffffLL &&
+                                   (uint64_t)n_nodes * (uint64_t)B * 4u <= 0xffffffffull;
+    bool dataflow = false;
+    if (flags & ASNN_FLAG_DATAFLOW) {
+        if (!workspace) return ASNN_ERR_NULL;
+        if (!dataflow_possible && n_levels > 1) return ASNN_ERR_SIZE;
+        dataflow = dataflow_possible;
+    } else if (!(flags & ASNN_FLAG_LEVEL_LAUNCHES) && dataflow_possible) {
+        dataflow = (double)n_edges * (double)B / (double)(n_levels - 1) < kDataflowMaxLevelWork;
+    }
+    if (dataflow && (((uintptr_t)workspace & 255u) != 0 || workspace_bytes < asnn_activate_workspace_bytes(n_nodes, B)))
+        return ASNN_ERR_WORKSPACE;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool f32 = (flags & ASNN_FLAG_ACC_F32) != 0;
     const int raw = (flags & ASNN_FLAG_RAW_INPUTS) ? 1 : 0;
-    LevelArgs a{row_ptr, col, w_packed, V, B, s};
+    LevelArgs a{packed->row_ptr, packed->col, packed->w, V, B, s};
 
-    for (int l = 0; l < n_levels; ++l) {
-        const int32_t *lp = level_ptr_host + ASNN_CLASSES * l;
-        const int hb = lp[0], mb = lp[1], lb = lp[2], le = lp[3];
-        if (l == 0) {
-            // Level 0 has no incoming connections.  Rows that are no sensors get
-            // sigmoid(0); when every row of the level is a sensor the fill is skipped.
-            if (le - hb != n_inputs)
-                ASNN_TRY(f32 ? launch_level_any<float>(a, hb, mb, lb, le) : launch_level_any<double>(a, hb, mb, lb, le));
-            if (n_inputs > 0) {
-                const unsigned blocks = blocks_for((size_t)n_inputs * (size_t)B, 256, 8192);
-                if (f32)
-                    hipLaunchKernelGGL(stage_inputs_kernel<float>, dim3(blocks), dim3(256), 0, s, input_ids, inv_perm, X,
-                                       V, n_inputs, n_nodes, B, raw);
-                else
-                    hipLaunchKernelGGL(stage_inputs_kernel<double>, dim3(blocks), dim3(256), 0, s, input_ids, inv_perm,
-                                       X, V, n_inputs, n_nodes, B, raw);
-                ASNN_HIP_TRY(hipGetLastError());
-            }
-            continue;
+    // Level 0 has no incoming connections.  Rows that are no sensors get sigmoid(0); when every
+    // row of the level is a sensor the fill is skipped.
+    {
+        const int hb = level_ptr_host[0], mb = level_ptr_host[1], lb = level_ptr_host[2], le = level_ptr_host[3];
+        if (le - hb != n_inputs)
+            ASNN_TRY(f32 ? launch_level_any<float>(a, hb, mb, lb, le) : launch_level_any<double>(a, hb, mb, lb, le));
+        if (n_inputs > 0) {
+            const unsigned blocks = blocks_for((size_t)n_inputs * (size_t)B, 256, 8192);
+            if (f32)
+                hipLaunchKernelGGL(stage_inputs_kernel<float>, dim3(blocks), dim3(256), 0, s, input_ids,
+                                   (const int32_t *)packed->inv_perm, X, V, n_inputs, n_nodes, B, raw);
+            else
+                hipLaunchKernelGGL(stage_inputs_kernel<double>, dim3(blocks), dim3(256), 0, s, input_ids,
+                                   (const int32_t *)packed->inv_perm, X, V, n_inputs, n_nodes, B, raw);
+            ASNN_HIP_TRY(hipGetLastError());
         }
-        ASNN_TRY(f32 ? launch_level_any<float>(a, hb, mb, lb, le) : launch_level_any<double>(a, hb, mb, lb, le));
+    }
+    if (dataflow) {
+        static int cus = 0;
+        if (cus == 0) {
+            int dev = 0;
+            hipDeviceProp_t prop;
+            ASNN_HIP_TRY(hipGetDevice(&dev));
+            ASNN_HIP_TRY(hipGetDeviceProperties(&prop, dev));
+            cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
+        }
+        ActivateWorkspace ws = carve_activate(workspace, n_nodes, B);
+        const size_t n_flags = (size_t)(n_nodes - first_row) * (size_t)tiles;
+        hipLaunchKernelGGL(dataflow_reset_kernel, dim3(blocks_for(n_flags, 256, 2048)), dim3(256), 0, s, ws.ready, n_flags,
+                           ws.ctl);
+        ASNN_HIP_TRY(hipGetLastError());
+        DataflowArgs d{packed->unit_ptr, packed->first_unit, (int)n_work, first_row,
+                       (uint32_t)((uint64_t)n_nodes * (uint64_t)B * 4u), ws.ready, ws.ctl, cus};
+        ASNN_TRY(f32 ? launch_dataflow_any<float>(a, d) : launch_dataflow_any<double>(a, d));
+    } else {
+        for (int l = 1; l < n_levels; ++l) {
+            const int32_t *lp = level_ptr_host + ASNN_CLASSES * l;
+            ASNN_TRY(f32 ? launch_level_any<float>(a, lp[0], lp[1], lp[2], lp[3])
+                         : launch_level_any<double>(a, lp[0], lp[1], lp[2], lp[3]));
+        }
     }
     if (Y && n_outputs > 0) {
         const unsigned blocks = blocks_for((size_t)n_outputs * (size_t)B, 256, 8192);
-        hipLaunchKernelGGL(extract_outputs_kernel, dim3(blocks), dim3(256), 0, s, output_ids, inv_perm,
-                           (const float *)V, Y, n_outputs, n_nodes, B);
+        hipLaunchKernelGGL(extract_outputs_kernel, dim3(blocks), dim3(256), 0, s, output_ids,
+                           (const int32_t *)packed->inv_perm, (const float *)V, Y, n_outputs, n_nodes, B);
         ASNN_HIP_TRY(hipGetLastError());
     }
     return ASNN_OK;

@@ -23,6 +23,7 @@ extern "C" const char *asnn_strerror(int code) {
         case ASNN_ERR_HIP: return "a HIP runtime call failed (see asnn_last_hip_error)";
         case ASNN_ERR_LEVEL_ORDER: return "level[] does not increase along a connection";
         case ASNN_ERR_NO_DEVICE: return "no HIP device available";
+        case ASNN_ERR_TIMEOUT: return "a dataflow wait exceeded its time limit";
         default: return "unknown error";
     }
 }

@@ -97,11 +97,38 @@ __global__ void gather_edges_kernel(const uint32_t *__restrict__ sorted_edge, co
     }
 }
 
+
+// Work units: every (level, class) segment of packed rows is cut into groups
+// of 1 (heavy), 4 (medium) or 16 (light) rows.  seg_units[k] = groups of key k.
+__device__ __host__ inline int unit_rows_of_class(int cls) { return cls == 0 ? 1 : (cls == 1 ? 4 : 16); }
+
+__global__ void segment_units_kernel(const int32_t *__restrict__ level_ptr, int32_t n_keys,
+                                     int32_t *__restrict__ seg_units) {
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k > n_keys) return;
+    if (k == n_keys) { seg_units[k] = 0; return; }
+    const int g = unit_rows_of_class(k % ASNN_CLASSES);
+    seg_units[k] = (level_ptr[k + 1] - level_ptr[k] + g - 1) / g;
+}
+
+// unit_ptr[u] = first packed row of unit u; unit_ptr[n_units] = n_nodes.
+__global__ void unit_ptr_kernel(const uint32_t *__restrict__ sorted_keys, const int32_t *__restrict__ level_ptr,
+                                const int32_t *__restrict__ seg_unit_start, int32_t n_nodes, int32_t n_keys,
+                                int32_t *__restrict__ unit_ptr) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i > n_nodes) return;
+    if (i == n_nodes) { unit_ptr[seg_unit_start[n_keys]] = n_nodes; return; }
+    const int k = (int)sorted_keys[i];
+    const int g = unit_rows_of_class(k % ASNN_CLASSES);
+    const int off = i - level_ptr[k];
+    if (off % g == 0) unit_ptr[seg_unit_start[k] + off / g] = i;
+}
+
 }  // namespace
 
 struct PackWorkspace {
     int *err;
-    int32_t *indeg, *packed_deg, *tmp;
+    int32_t *indeg, *packed_deg, *seg_units, *tmp;
     uint32_t *keys_a, *vals_a, *keys_b, *vals_b;
     size_t bytes;
 };
@@ -114,6 +141,7 @@ static PackWorkspace carve_pack(void *ws, int32_t n_nodes, int64_t n_edges) {
     w.err = c.take<int>(64);
     w.indeg = c.take<int32_t>(n + 1);
     w.packed_deg = c.take<int32_t>(n + 1);
+    w.seg_units = c.take<int32_t>((size_t)ASNN_CLASSES * n + 2);     // n_levels <= n_nodes
     w.keys_a = c.take<uint32_t>(m);
     w.vals_a = c.take<uint32_t>(m);
     w.keys_b = c.take<uint32_t>(m);
@@ -133,14 +161,19 @@ extern "C" size_t asnn_pack_workspace_bytes(int32_t n_nodes, int64_t n_edges) {
     return carve_pack(nullptr, n_nodes, n_edges).bytes;
 }
 
-extern "C" int asnn_pack_csr(int32_t n_nodes, int64_t n_edges, int32_t n_levels, const int32_t *src, const int32_t *dst,
-                             const float *w, const int32_t *level, int32_t *level_ptr, int32_t *level_ptr_host,
-                             int32_t *perm, int32_t *inv_perm, int32_t *row_ptr, int32_t *col, float *w_packed,
-                             void *workspace, size_t workspace_bytes, void *stream) {
+extern "C" int asnn_pack_csr(const int32_t *src, const int32_t *dst, const float *w, const int32_t *level,
+                             asnn_packed *packed, void *workspace, size_t workspace_bytes, void *stream) {
+    if (!packed) return ASNN_ERR_NULL;
+    const int32_t n_nodes = packed->n_nodes, n_levels = packed->n_levels;
+    const int64_t n_edges = packed->n_edges;
+    int32_t *level_ptr = packed->level_ptr, *level_ptr_host = packed->level_ptr_host, *perm = packed->perm,
+            *inv_perm = packed->inv_perm, *row_ptr = packed->row_ptr, *col = packed->col, *unit_ptr = packed->unit_ptr;
+    float *w_packed = packed->w;
     if (n_nodes <= 0 || n_edges < 0 || n_edges >= (int64_t)INT32_MAX || n_levels <= 0 ||
         n_levels > n_nodes || n_levels >= (1 << 29))
         return ASNN_ERR_SIZE;
-    if (!level || !level_ptr || !level_ptr_host || !perm || !inv_perm || !row_ptr || !workspace) return ASNN_ERR_NULL;
+    if (!level || !level_ptr || !level_ptr_host || !perm || !inv_perm || !row_ptr || !unit_ptr || !workspace)
+        return ASNN_ERR_NULL;
     if (n_edges > 0 && (!src || !dst || !w || !col || !w_packed)) return ASNN_ERR_NULL;
     if (((uintptr_t)workspace & 255u) != 0 || workspace_bytes < asnn_pack_workspace_bytes(n_nodes, n_edges))
         return ASNN_ERR_WORKSPACE;
@@ -169,6 +202,17 @@ extern "C" int asnn_pack_csr(int32_t n_nodes, int64_t n_edges, int32_t n_levels,
                        (const uint32_t *)ks, n_nodes, n_keys, level_ptr);
     ASNN_HIP_TRY(hipGetLastError());
     ASNN_TRY(exclusive_scan_i32(ws.packed_deg, row_ptr, n + 1, ws.tmp, s));
+    // work units (uses the sorted node keys, so before the edge sort recycles the buffers)
+    hipLaunchKernelGGL(segment_units_kernel, dim3(blocks_for((size_t)n_keys + 1, kThreads)), dim3(kThreads), 0, s,
+                       (const int32_t *)level_ptr, n_keys, ws.seg_units);
+    ASNN_HIP_TRY(hipGetLastError());
+    ASNN_TRY(exclusive_scan_i32(ws.seg_units, ws.seg_units, (size_t)n_keys + 1, ws.tmp, s));
+    hipLaunchKernelGGL(unit_ptr_kernel, dim3(blocks_for(n + 1, kThreads)), dim3(kThreads), 0, s, (const uint32_t *)ks,
+                       (const int32_t *)level_ptr, (const int32_t *)ws.seg_units, n_nodes, n_keys, unit_ptr);
+    ASNN_HIP_TRY(hipGetLastError());
+    int32_t host_units[2] = {0, 0};      // {first unit above level 0, number of units}
+    ASNN_HIP_TRY(hipMemcpyAsync(&host_units[0], ws.seg_units + ASNN_CLASSES, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    ASNN_HIP_TRY(hipMemcpyAsync(&host_units[1], ws.seg_units + n_keys, sizeof(int32_t), hipMemcpyDeviceToHost, s));
 
     // edges: stable sort by packed destination keeps each node's edge-list order
     if (n_edges > 0) {
@@ -187,5 +231,7 @@ extern "C" int asnn_pack_csr(int32_t n_nodes, int64_t n_edges, int32_t n_levels,
     ASNN_HIP_TRY(hipMemcpyAsync(level_ptr_host, level_ptr, sizeof(int32_t) * ((size_t)n_keys + 1),
                                 hipMemcpyDeviceToHost, s));
     ASNN_HIP_TRY(hipStreamSynchronize(s));
+    packed->first_unit = host_units[0];
+    packed->n_units = host_units[1];
     return host_err;
 }

@@ -37,7 +37,7 @@ def test_every_declared_symbol_is_exported(lib):
 def test_error_strings(lib):
     assert lib.asnn_strerror(0) == b"ok"
     seen = set()
-    for code in range(-10, 0):
+    for code in range(-11, 0):
         s = lib.asnn_strerror(code)
         assert s and s != b"unknown error" and s not in seen
         seen.add(s)
@@ -81,21 +81,42 @@ def test_argument_checks_need_no_device(lib):
     assert lib.asnn_build_levels(4, 2, fake, fake, None, 0, fake, ctypes.byref(nl), fake, 16, None) == -7
     assert lib.asnn_build_levels(4, 2, fake, fake, None, 0, fake, ctypes.byref(nl), ctypes.c_void_p(264), 1 << 20, None) == -7
     assert lib.asnn_build_levels(0, 0, None, None, None, 0, None, ctypes.byref(nl), None, 0, None) == 0 and nl.value == 0
+    import paper_2005_04347_amd.binding as b
     lph = (i32 * 4)(0, 0, 0, 4)
-    assert lib.asnn_pack_csr(0, 0, 1, None, None, None, fake, fake, lph, fake, fake, fake, None, None, fake, 1 << 20, None) == -2
-    assert lib.asnn_pack_csr(4, 0, 9, None, None, None, fake, fake, lph, fake, fake, fake, None, None, fake, 1 << 20, None) == -2
-    assert lib.asnn_pack_csr(4, 0, 1, None, None, None, None, fake, lph, fake, fake, fake, None, None, fake, 1 << 20, None) == -1
-    assert lib.asnn_pack_csr(4, 0, 1, None, None, None, fake, fake, lph, fake, fake, fake, None, None, fake, 8, None) == -7
+    F = 256
+
+    def rec(**k):
+        r = b.AsnnPacked(n_nodes=k.get("n", 4), n_levels=k.get("L", 1), n_edges=k.get("e", 0), n_units=1, first_unit=1,
+                         level_ptr_host=ctypes.addressof(k.get("lph", lph)) if k.get("lph", lph) is not None else None,
+                         level_ptr=F, perm=F, inv_perm=F, row_ptr=F, col=None, w=None, unit_ptr=F)
+        for name in k.get("null", ()):
+            setattr(r, name, None)
+        return r
+
+    pack = lambda r, ws=fake, nbytes=1 << 20: lib.asnn_pack_csr(None, None, None, fake, ctypes.byref(r), ws, nbytes, None)
+    assert lib.asnn_pack_csr(None, None, None, fake, None, fake, 1 << 20, None) == -1
+    assert pack(rec(n=0)) == -2
+    assert pack(rec(L=9)) == -2
+    assert pack(rec(null=("perm",))) == -1
+    assert pack(rec(null=("unit_ptr",))) == -1
+    assert pack(rec(), nbytes=8) == -7
+    assert lib.asnn_pack_csr(None, None, None, None, ctypes.byref(rec()), fake, 1 << 20, None) == -1
     # activate: sizes, NULLs, alignment of V, and a level table that does not cover the rows
-    args = lambda **k: [k.get("n", 4), 0, 1, k.get("lph", lph), fake, None, None, fake, fake, k.get("n_in", 1), None, 0,
-                        fake, k.get("B", 2), k.get("V", fake), None, 0, None]
-    assert lib.asnn_activate(*args(B=0)) == -2
-    assert lib.asnn_activate(*args(n=0)) == -2
-    assert lib.asnn_activate(*args(V=None)) == -1
-    assert lib.asnn_activate(*args(V=ctypes.c_void_p(260))) == -2
-    assert lib.asnn_activate(*args(lph=(i32 * 4)(0, 0, 0, 3))) == -2
-    assert lib.asnn_activate(*args(lph=(i32 * 4)(0, 5, 4, 4))) == -2
-    assert lib.asnn_activate(*args(lph=None)) == -1
+    act = lambda r, B=2, V=fake, flags=0, ws=None: lib.asnn_activate(ctypes.byref(r), fake, 1, None, 0, fake, B, V, None,
+                                                                     ws, 0, flags, None)
+    assert lib.asnn_activate(None, fake, 1, None, 0, fake, 2, fake, None, None, 0, 0, None) == -1
+    assert act(rec(), B=0) == -2
+    assert act(rec(n=0)) == -2
+    assert act(rec(), V=None) == -1
+    assert act(rec(), V=ctypes.c_void_p(260)) == -2
+    assert act(rec(lph=(i32 * 4)(0, 0, 0, 3))) == -2
+    assert act(rec(lph=(i32 * 4)(0, 5, 4, 4))) == -2
+    assert act(rec(lph=None)) == -1
+    assert act(rec(), flags=4 | 8) == -2                      # both schedules forced
+    assert act(rec(), flags=8) == -1                          # dataflow forced without a workspace
+    assert lib.asnn_activate_workspace_bytes(0, 4) == 0
+    small, big = lib.asnn_activate_workspace_bytes(1000, 64), lib.asnn_activate_workspace_bytes(1000, 1024)
+    assert 0 < small < big and small % 256 == 0
 
 
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):

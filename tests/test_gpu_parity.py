@@ -47,13 +47,33 @@ def expected_pack(wl, level, n_levels, heavy=256, medium=32):
     return perm, inv, level_ptr, row_ptr, col, w
 
 
-def run_gpu(amd, wl, flags=0, poison=True, X=None):
-    net = amd.Network(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.output_ids)
+LEVELS, DATAFLOW = 4, 8          # ASNN_FLAG_LEVEL_LAUNCHES, ASNN_FLAG_DATAFLOW
+SCHEDULES = [LEVELS, DATAFLOW]
+
+
+def run_gpu(amd, wl, flags=0, poison=True, X=None, net=None):
+    """One activation on a NaN-poisoned V (a row read before it is written shows up as NaN)."""
+    if net is None:
+        net = amd.Network(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.output_ids)
     X = wl.X if X is None else X
     V = torch.full((wl.n_nodes, X.shape[1]), float("nan"), device="cuda:0") if poison else None
     V, Y = net.activate(X, V=V, flags=flags)
-    torch.cuda.synchronize()
+    net.check(X.shape[1])            # synchronises; raises if a dataflow wait gave up
     return net, V, Y
+
+
+def expected_units(level_ptr, n_levels):
+    """numpy statement of the work units: every (level, class) segment cut into groups of 1 / 4 / 16 rows."""
+    starts = []
+    first_unit = None
+    for k in range(3 * n_levels):
+        if k == 3:
+            first_unit = len(starts)
+        g = (1, 4, 16)[k % 3]
+        starts += list(range(level_ptr[k], level_ptr[k + 1], g))
+    if first_unit is None:
+        first_unit = len(starts)
+    return np.array(starts + [level_ptr[-1]], dtype=np.int32), first_unit
 
 
 @pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
@@ -75,35 +95,44 @@ def test_small_configs_levels_pack_activation(amd, idx):
     assert (g.row_ptr.cpu().numpy() == row_ptr).all()
     assert (g.col.cpu().numpy() == col).all()
     assert (g.w.cpu().numpy() == w).all()
+    units, first_unit = expected_units(level_ptr, nl_o)
+    assert g.n_units == len(units) - 1 and g.first_unit == first_unit
+    assert (g.unit_ptr.cpu().numpy()[: g.n_units + 1] == units).all()
     want = oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.X)
-    got = net.values_original_order(V).cpu().numpy()
-    assert np.isfinite(got).all()
-    err = float(np.abs(got.astype(np.float64) - want).max())
-    assert err <= TIGHT, err
-    assert (Y.cpu().numpy() == got[wl.output_ids]).all()
-    # fp32 mode still meets the stated bar on these sizes
-    _, V32, _ = run_gpu(amd, wl, flags=amd.FLAG_ACC_F32)
-    got32 = net.values_original_order(V32).cpu().numpy()
-    err32 = float(np.abs(got32.astype(np.float64) - want).max())
-    # fp32 accumulation is the fast mode, not the parity mode: with weights in
-    # [-2,2] (config 5) or in-degrees in the thousands (config 4) its rounding
-    # noise alone exceeds 1e-5 (the oracle's own fp32 variant shows the same).
-    assert err32 <= (TOL if idx <= 3 else 30 * TOL), err32
+    results = []
+    for sched in SCHEDULES:
+        _, V, Y = run_gpu(amd, wl, flags=sched, net=net)
+        got = net.values_original_order(V).cpu().numpy()
+        assert np.isfinite(got).all()
+        err = float(np.abs(got.astype(np.float64) - want).max())
+        assert err <= TIGHT, (sched, err)
+        assert (Y.cpu().numpy() == got[wl.output_ids]).all()
+        results.append(got)
+        # fp32 accumulation is the fast mode, not the parity mode: with weights in
+        # [-2,2] (config 5) or in-degrees in the thousands (config 4) its rounding
+        # noise alone exceeds 1e-5 (the oracle's own fp32 variant shows the same).
+        _, V32, _ = run_gpu(amd, wl, flags=sched | amd.FLAG_ACC_F32, net=net)
+        got32 = net.values_original_order(V32).cpu().numpy()
+        err32 = float(np.abs(got32.astype(np.float64) - want).max())
+        assert err32 <= (TOL if idx <= 3 else 30 * TOL), (sched, err32)
+    assert (results[0] == results[1]).all()          # both schedules give the same bits
 
 
 @pytest.mark.parametrize("B", [1, 2, 3, 4, 6, 8, 12, 20, 36, 64, 100, 127, 128, 130, 256, 260, 516])
 def test_batch_widths_cover_every_lane_layout(amd, B):
     """Every (vector width, lanes-per-tile) kernel variant, ragged tiles included."""
     wl = layered_skip(seed=5, n_nodes=700, n_inputs=19, n_outputs=9, n_levels=7, B=B, mean_extra_degree=9.0)
-    net, V, _ = run_gpu(amd, wl)
     want = oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.X)
-    got = net.values_original_order(V).cpu().numpy()
-    err = float(np.abs(got.astype(np.float64) - want).max())
-    assert err <= TIGHT, err
-    _, V32, _ = run_gpu(amd, wl, flags=amd.FLAG_ACC_F32)
-    got32 = net.values_original_order(V32).cpu().numpy()
-    err32 = float(np.abs(got32.astype(np.float64) - want).max())
-    assert err32 <= TOL, err32
+    net = None
+    for sched in SCHEDULES:
+        net, V, _ = run_gpu(amd, wl, flags=sched, net=net)
+        got = net.values_original_order(V).cpu().numpy()
+        err = float(np.abs(got.astype(np.float64) - want).max())
+        assert err <= TIGHT, (sched, err)
+        _, V32, _ = run_gpu(amd, wl, flags=sched | amd.FLAG_ACC_F32, net=net)
+        got32 = net.values_original_order(V32).cpu().numpy()
+        err32 = float(np.abs(got32.astype(np.float64) - want).max())
+        assert err32 <= TOL, (sched, err32)
 
 
 def _heavy_workload(B, seed=3):
@@ -135,26 +164,36 @@ def _heavy_workload(B, seed=3):
 @pytest.mark.parametrize("B", [1, 5, 64, 256, 1024])
 def test_heavy_rows_and_non_sensor_root(amd, B):
     wl, root = _heavy_workload(B)
-    net, V, _ = run_gpu(amd, wl)
-    lp = net.graph.level_ptr_host
-    assert lp[4] - lp[3] > 0 and lp[7] - lp[6] > 0          # heavy ranges of levels 1 and 2 are populated
-    assert lp[5] - lp[4] > 0 and lp[6] - lp[5] > 0          # and so are the medium and light ones of level 1
     want = oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.X)
-    got = net.values_original_order(V).cpu().numpy()
-    assert (got[root] == np.float32(0.5)).all()
-    assert np.abs(got.astype(np.float64) - want).max() <= TIGHT
-    _, V32, _ = run_gpu(amd, wl, flags=amd.FLAG_ACC_F32)
-    got32 = net.values_original_order(V32).cpu().numpy()
-    err32 = float(np.abs(got32.astype(np.float64) - want).max())
-    assert err32 <= 30 * TOL, err32      # thousands of fp32 terms per sum: fast mode only
+    net = None
+    for sched in SCHEDULES:
+        net, V, _ = run_gpu(amd, wl, flags=sched, net=net)
+        lp = net.graph.level_ptr_host
+        assert lp[4] - lp[3] > 0 and lp[7] - lp[6] > 0          # heavy ranges of levels 1 and 2 are populated
+        assert lp[5] - lp[4] > 0 and lp[6] - lp[5] > 0          # and so are the medium and light ones of level 1
+        got = net.values_original_order(V).cpu().numpy()
+        assert (got[root] == np.float32(0.5)).all()
+        err = float(np.abs(got.astype(np.float64) - want).max())
+        assert err <= TIGHT, (sched, err)
+        _, V32, _ = run_gpu(amd, wl, flags=sched | amd.FLAG_ACC_F32, net=net)
+        got32 = net.values_original_order(V32).cpu().numpy()
+        err32 = float(np.abs(got32.astype(np.float64) - want).max())
+        assert err32 <= 30 * TOL, (sched, err32)      # thousands of fp32 terms per sum: fast mode only
 
 
 def test_deterministic_and_raw_inputs(amd):
     wl = make_config(3, "small")
-    net, V1, Y1 = run_gpu(amd, wl)
-    V2, Y2 = net.activate(wl.X)
+    net, V1, Y1 = run_gpu(amd, wl, flags=LEVELS)
+    for sched in (LEVELS, DATAFLOW, 0, DATAFLOW):
+        V2, Y2 = net.activate(wl.X, flags=sched)
+        net.check(wl.B)
+        assert torch.equal(V1, V2) and torch.equal(Y1, Y2)
+    # without a workspace only level launches are possible; forcing dataflow is refused
+    V2, _ = net.activate(wl.X, use_workspace=False)
     torch.cuda.synchronize()
-    assert torch.equal(V1, V2) and torch.equal(Y1, Y2)
+    assert torch.equal(V1, V2)
+    with pytest.raises(amd.AsnnError):
+        net.activate(wl.X, flags=DATAFLOW, use_workspace=False)
     V3, _ = net.activate(wl.X, flags=amd.FLAG_RAW_INPUTS)
     want = oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.X, raw_inputs=True)
     got = net.values_original_order(V3).cpu().numpy()
@@ -168,7 +207,7 @@ def test_saturation_gives_exact_zero_and_one(amd):
     src = np.zeros(8192, dtype=np.int32)
     dst = np.concatenate([np.full(4096, 1), np.full(4096, 2)]).astype(np.int32)
     w = np.concatenate([np.full(4096, -1.0), np.full(4096, 1.0)]).astype(np.float32)
-    for flags in (0, 2):
+    for flags in (LEVELS, LEVELS | 2, DATAFLOW, DATAFLOW | 2):
         wl = Workload("sat", 3, src, dst, w, np.array([0], np.int32), np.array([1, 2], np.int32),
                       np.zeros((1, 4), np.float32))
         _, V, Y = run_gpu(amd, wl, flags=flags)
@@ -177,7 +216,7 @@ def test_saturation_gives_exact_zero_and_one(amd):
     wl = Workload("sat2", 2, np.array([0], np.int32), np.array([1], np.int32), np.array([-1.0], np.float32),
                   np.array([0], np.int32), np.array([1], np.int32),
                   np.array([[30.0, 1000.0, 3.0e38, -3.0e38]], np.float32))
-    for flags in (1, 3):
+    for flags in (LEVELS | 1, LEVELS | 3, DATAFLOW | 1, DATAFLOW | 3):
         _, V, Y = run_gpu(amd, wl, flags=flags)
         y = Y.cpu().numpy()[0]
         assert (y[:3] == 0.0).all() and y[3] == 1.0
@@ -188,19 +227,21 @@ def test_degenerate_networks(amd):
     # no connections at all: sensors squash, the other node gives 0.5
     wl = Workload("noedge", 3, np.zeros(0, np.int32), np.zeros(0, np.int32), np.zeros(0, np.float32),
                   np.array([2, 0], np.int32), np.array([1, 2], np.int32), np.array([[0.0, 1.0], [0.25, 0.5]], np.float32))
-    net, V, Y = run_gpu(amd, wl)
-    assert net.n_levels == 1
     want = oracle.activate(3, wl.src, wl.dst, wl.w, wl.input_ids, wl.X)
-    got = net.values_original_order(V).cpu().numpy()
-    assert np.abs(got - want).max() <= TIGHT and (got[1] == 0.5).all()
+    for sched in (0, LEVELS, DATAFLOW):
+        net, V, Y = run_gpu(amd, wl, flags=sched)
+        assert net.n_levels == 1
+        got = net.values_original_order(V).cpu().numpy()
+        assert np.abs(got - want).max() <= TIGHT and (got[1] == 0.5).all()
     # a single node, a single chain
     wl = Workload("chain", 5, np.arange(4, dtype=np.int32), np.arange(1, 5, dtype=np.int32),
                   np.array([1.0, -2.0, 0.5, 3.0], np.float32), np.array([0], np.int32), np.array([4], np.int32),
                   np.array([[0.3]], np.float32))
-    net, V, Y = run_gpu(amd, wl)
-    assert net.n_levels == 5
     want = oracle.activate(5, wl.src, wl.dst, wl.w, wl.input_ids, wl.X)
-    assert np.abs(net.values_original_order(V).cpu().numpy() - want).max() <= TIGHT
+    for sched in (0, LEVELS, DATAFLOW):
+        net, V, Y = run_gpu(amd, wl, flags=sched)
+        assert net.n_levels == 5
+        assert np.abs(net.values_original_order(V).cpu().numpy() - want).max() <= TIGHT
 
 
 def test_error_codes_from_device_checks(amd):
@@ -237,12 +278,13 @@ FULL_COLUMNS = {1: None, 2: None, 3: 48, 4: 16, 5: 12}
 
 @pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
 def test_full_size_configs(amd, idx):
-    """The five workloads at full size in the launch configuration the
-    benchmark times.  Levels: every node, bit-exact.  Activations: batch columns
-    are independent, so the oracle evaluates a spread subset of columns (all
-    nodes of those columns) and the same columns of the GPU result must agree."""
+    """The five workloads at full size, in the default schedule (the one the
+    benchmark times) and in both forced schedules.  Levels: every node,
+    bit-exact.  Activations: batch columns are independent, so the oracle
+    evaluates a spread subset of columns (all nodes of those columns) and the
+    same columns of the GPU result must agree."""
     wl = make_config(idx, "full")
-    net, V, Y = run_gpu(amd, wl, poison=True)
+    net = amd.Network(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.output_ids)
     lv = net.level.cpu().numpy()
     lv_o, nl_o = oracle.levels(wl.n_nodes, wl.src, wl.dst)
     assert net.n_levels == nl_o and (lv == lv_o).all()
@@ -252,12 +294,17 @@ def test_full_size_configs(amd, idx):
     cols = np.arange(wl.B) if ncol is None else np.unique(np.linspace(0, wl.B - 1, ncol).astype(int))
     want = oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, np.ascontiguousarray(wl.X[:, cols]))
     inv = net.graph.inv_perm.long()
-    got = V[:, torch.as_tensor(cols, device=V.device)][inv].cpu().numpy()
-    assert np.isfinite(got).all()
-    err = float(np.abs(got.astype(np.float64) - want).max())
-    print(f"config {idx}: N={wl.n_nodes} E={wl.n_edges} B={wl.B} L={nl_o} columns={len(cols)} max_abs_err={err:.3e}")
-    assert err <= TOL, err
-    y = Y[:, torch.as_tensor(cols, device=V.device)].cpu().numpy()
-    assert (y == got[wl.output_ids]).all()
-    # nothing outside the sampled columns is left unwritten
-    assert not torch.isnan(V).any()
+    tcols = torch.as_tensor(cols, device="cuda:0")
+    for sched in (0, LEVELS, DATAFLOW):
+        _, V, Y = run_gpu(amd, wl, flags=sched, net=net)
+        got = V[:, tcols][inv].cpu().numpy()
+        assert np.isfinite(got).all()
+        err = float(np.abs(got.astype(np.float64) - want).max())
+        print(f"config {idx} schedule {sched}: N={wl.n_nodes} E={wl.n_edges} B={wl.B} L={nl_o} "
+              f"columns={len(cols)} max_abs_err={err:.3e}")
+        assert err <= TOL, (sched, err)
+        y = Y[:, tcols].cpu().numpy()
+        assert (y == got[wl.output_ids]).all()
+        # nothing outside the sampled columns is left unwritten
+        assert not torch.isnan(V).any()
+        del V, Y
