@@ -12,7 +12,8 @@
 // connections are shared by 4 (medium) or 16 (heavy) wavefronts whose partial
 // sums meet in LDS in wave order.  Nothing depends on timing: the same inputs
 // give the same bits.  The layer barrier is the boundary between two launches
-// on the stream.
+// on the stream; a second schedule (further down) replaces the barriers by
+// per-row waiting inside one persistent launch.
 //
 // Arithmetic: products and sums in ACC (double by default, float with
 // ASNN_FLAG_ACC_F32), sigmoid(x) = 1/(1+e^(-4.97x)) in ACC, one rounding to
@@ -232,17 +233,19 @@ __global__ __launch_bounds__(kMixedBlock) void gather_mixed_kernel(const int32_t
 
 // ---------------------------------------------------------------- dataflow
 // One persistent launch instead of one launch per level.  Workgroups claim
-// work items (unit, tile) in packed order from a global counter.  A row's
-// wavefront first polls the ready flags of its own source rows, then gathers;
-// when it has stored its tile it raises the row's flag.  An item only waits
+// work items (unit, tile) in packed order from a global counter.  Before the
+// launch every row above level 0 is filled with a signalling-NaN pattern that
+// no arithmetic result can have; a wavefront gathers its source tiles and
+// simply re-reads those that still show the pattern, so the data is its own
+// ready flag and a row costs one device-scope round trip after its last
+// source, not a flag round trip plus a data round trip.  An item only waits
 // for items with a smaller index, and an item is claimed by a running
 // workgroup after every smaller item was claimed, so the smallest unfinished
 // item never waits for anything: no deadlock for any grid size.
 //
-// Cross-workgroup visibility without cache flushes: V tiles and flags are read
-// and written with device-scope (sc1) accesses, which bypass the per-XCD L2
-// for lines that another XCD may have written; the writer waits for its stores
-// to complete (vmcnt) before it raises the flag.
+// Cross-workgroup visibility without cache flushes: V tiles are read and
+// written with device-scope (sc1) accesses, which bypass the per-XCD L2 for
+// lines that another XCD may have written.
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
@@ -250,6 +253,9 @@ typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
 constexpr int kAuxDeviceScope = 16;                 // cache-policy bit sc1
 constexpr int kBufferFlags = 0x27000;               // raw 32-bit buffer, gfx9 descriptor word 3
 constexpr long long kWaitTicks = 200000000LL;       // 2 s of the 100 MHz wall clock
+// "Not written yet": exponent all ones, quiet bit clear, payload set.  Arithmetic only ever
+// produces quiet NaNs, so no stored activation has these bits.
+constexpr unsigned int kNotReady = 0x7fa5c0deu;
 
 struct DataflowCtl {
     int head;       // next work item
@@ -273,61 +279,74 @@ __device__ inline void store_vec_device_scope(__amdgpu_buffer_rsrc_t r, uint32_t
     if constexpr (VEC == 1) { __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, in[0]), r, byte_off, 0, kAuxDeviceScope); }
 }
 
-// Blocks until every lane's source row (src, meaningful where `mine`) has
-// raised its flag for this tile.  Gives up after kWaitTicks or when another
-// wave already gave up, so every wave leaves the kernel.
-__device__ inline void wait_for_sources(bool mine, int src, int first_row, int tiles, int tile, const int *ready,
-                                        DataflowCtl *ctl) {
-    bool pending = mine && src >= first_row;
-    if (__any(pending)) {
-        const long long t0 = wall_clock64();
-        int spins = 0;
-        for (;;) {
-            if (pending) {
-                const int f = __hip_atomic_load(&ready[(size_t)(src - first_row) * (size_t)tiles + tile], __ATOMIC_RELAXED,
-                                                __HIP_MEMORY_SCOPE_AGENT);
-                pending = (f == 0);
-            }
-            if (!__any(pending)) break;
-            __builtin_amdgcn_s_sleep(1);
-            if ((++spins & 127) == 0) {
-                const int err = __hip_atomic_load(&ctl->error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if (err != 0 || wall_clock64() - t0 > kWaitTicks) {
-                    __hip_atomic_store(&ctl->error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    break;
-                }
-            }
-        }
-    }
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+template <int VEC>
+__device__ inline bool shows_not_ready(const float (&v)[VEC]) {
+    bool r = false;
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) r = r || (__builtin_bit_cast(unsigned int, v[j]) == kNotReady);
+    return r;
 }
 
-// row_sum with waiting: connections are taken 64 at a time (one per lane),
-// their sources awaited, then gathered with device-scope loads.
+// Bounded back-off between two attempts to read a tile that is not written yet.
+// Returns false when the wait must be abandoned (time limit, or another wave gave up).
+struct Patience {
+    long long t0 = 0;
+    int spins = 0;
+    __device__ inline bool again(DataflowCtl *ctl) {
+        if (spins == 0) t0 = wall_clock64();
+        __builtin_amdgcn_s_sleep(2);
+        if ((++spins & 63) == 0) {
+            const int err = __hip_atomic_load(&ctl->error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (err != 0 || wall_clock64() - t0 > kWaitTicks) {
+                __hip_atomic_store(&ctl->error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                return false;
+            }
+        }
+        return true;
+    }
+};
+
+// row_sum for the dataflow schedule: connections are taken 64 at a time (one
+// per lane) and gathered with device-scope loads; tiles of rows at or above
+// first_row that still hold the not-ready pattern are read again.
 template <int VEC, int LPG, typename ACC, int U>
 __device__ inline void row_sum_dataflow(const int32_t *__restrict__ col, const float *__restrict__ w,
                                         __amdgpu_buffer_rsrc_t vres, int B, int e_begin, int e_end, int c0, int first_row,
-                                        int tiles, int tile, const int *ready, DataflowCtl *ctl, ACC (&acc)[VEC]) {
+                                        DataflowCtl *ctl, ACC (&acc)[VEC]) {
     constexpr int G = kWave / LPG;
     const int lane = threadIdx.x & (kWave - 1);
 #pragma unroll
     for (int j = 0; j < VEC; ++j) acc[j] = ACC(0);
+    Patience patience;
     for (int eb = e_begin; eb < e_end; eb += kWave) {
         const int n = min(kWave, e_end - eb);
         const int my = eb + min(lane, n - 1);
         const int mc = col[my];
         const float mw = (lane < n) ? w[my] : 0.0f;
-        wait_for_sources(lane < n, mc, first_row, tiles, tile, ready, ctl);
         if constexpr (G == 1) {
             for (int i = 0; i < n; i += U) {
                 float vals[U][VEC];
                 float ww[U];
+                uint32_t off[U];
+                bool watch[U];          // wave-uniform: a real connection whose source is above level 0
 #pragma unroll
                 for (int k = 0; k < U; ++k) {
                     const int idx = min(i + k, n - 1);
                     const int ck = __builtin_amdgcn_readlane(mc, idx);
                     ww[k] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, mw), idx));
-                    load_vec_device_scope<VEC>(vres, ((uint32_t)ck * (uint32_t)B + (uint32_t)c0) * 4u, vals[k]);
+                    off[k] = ((uint32_t)ck * (uint32_t)B + (uint32_t)c0) * 4u;
+                    watch[k] = (i + k < n) && ck >= first_row;
+                    load_vec_device_scope<VEC>(vres, off[k], vals[k]);
+                }
+                for (;;) {
+                    bool retry = false;
+#pragma unroll
+                    for (int k = 0; k < U; ++k) {
+                        const bool again = watch[k] && __any(shows_not_ready<VEC>(vals[k]));     // wave-uniform
+                        if (again) load_vec_device_scope<VEC>(vres, off[k], vals[k]);
+                        retry = retry || again;
+                    }
+                    if (!retry || !patience.again(ctl)) break;
                 }
 #pragma unroll
                 for (int k = 0; k < U; ++k)
@@ -341,7 +360,8 @@ __device__ inline void row_sum_dataflow(const int32_t *__restrict__ col, const f
             for (int i = 0; i < n; i += G * U) {
                 float vals[U][VEC];
                 float ww[U];
-                bool ok[U];
+                uint32_t off[U];
+                bool ok[U], watch[U];   // per lane group
 #pragma unroll
                 for (int k = 0; k < U; ++k) {
                     const int idx = i + k * G + g;
@@ -349,7 +369,19 @@ __device__ inline void row_sum_dataflow(const int32_t *__restrict__ col, const f
                     const int sel = min(idx, n - 1);
                     const int ck = __shfl(mc, sel, kWave);
                     ww[k] = __shfl(mw, sel, kWave);
-                    load_vec_device_scope<VEC>(vres, ((uint32_t)ck * (uint32_t)B + (uint32_t)c0) * 4u, vals[k]);
+                    off[k] = ((uint32_t)ck * (uint32_t)B + (uint32_t)c0) * 4u;
+                    watch[k] = ok[k] && ck >= first_row;
+                    load_vec_device_scope<VEC>(vres, off[k], vals[k]);     // padded slots re-read a valid tile
+                }
+                for (;;) {
+                    bool mine = false;
+#pragma unroll
+                    for (int k = 0; k < U; ++k) {
+                        const bool again = watch[k] && shows_not_ready<VEC>(vals[k]);
+                        if (again) load_vec_device_scope<VEC>(vres, off[k], vals[k]);
+                        mine = mine || again;
+                    }
+                    if (!__any(mine) || !patience.again(ctl)) break;
                 }
 #pragma unroll
                 for (int k = 0; k < U; ++k)
@@ -369,10 +401,12 @@ __device__ inline void row_sum_dataflow(const int32_t *__restrict__ col, const f
     }
 }
 
-__global__ void dataflow_reset_kernel(int *ready, size_t n_flags, DataflowCtl *ctl) {
+// Marks every value of rows [first_row, n_nodes) as not written and resets the control block.
+__global__ void dataflow_reset_kernel(unsigned int *v_begin, size_t n_values, DataflowCtl *ctl) {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_flags; i += stride) ready[i] = 0;
-    if (blockIdx.x == 0 && threadIdx.x < 64) reinterpret_cast<int *>(ctl)[threadIdx.x] = (threadIdx.x == 2) ? kCtlMagic : 0;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_values; i += stride) v_begin[i] = kNotReady;
+    if (blockIdx.x == 0 && threadIdx.x < 64)
+        reinterpret_cast<int *>(ctl)[threadIdx.x] = (threadIdx.x == 2) ? kCtlMagic : 0;
 }
 
 template <int VEC, int LPG, typename ACC, int U>
@@ -381,7 +415,7 @@ __global__ __launch_bounds__(kMixedBlock) void dataflow_kernel(const int32_t *__
                                                                 const float *__restrict__ w, float *V, uint32_t v_bytes,
                                                                 int B, const int32_t *__restrict__ unit_ptr,
                                                                 int first_unit, int n_work, int tiles, int first_row,
-                                                                int *ready, DataflowCtl *ctl) {
+                                                                DataflowCtl *ctl) {
     constexpr int T = LPG * VEC;
     __shared__ ACC part[kMixedWaves][LPG * VEC];
     __shared__ int s_claim;
@@ -411,8 +445,7 @@ __global__ __launch_bounds__(kMixedBlock) void dataflow_kernel(const int32_t *__
             const int e0 = row_ptr[row], e1 = row_ptr[row + 1];
             const int chunk = (e1 - e0 + share - 1) / share;
             const int b0 = min(e0 + slice * chunk, e1), b1 = min(b0 + chunk, e1);
-            row_sum_dataflow<VEC, LPG, ACC, U>(col, w, vres, B, b0, b1, active ? c : 0, first_row, tiles, tile, ready,
-                                               ctl, acc);
+            row_sum_dataflow<VEC, LPG, ACC, U>(col, w, vres, B, b0, b1, active ? c : 0, first_row, ctl, acc);
         } else {
 #pragma unroll
             for (int j = 0; j < VEC; ++j) acc[j] = ACC(0);
@@ -432,21 +465,11 @@ __global__ __launch_bounds__(kMixedBlock) void dataflow_kernel(const int32_t *__
                 }
             }
         }
-        if (valid && slice == 0) {                     // wave-uniform
-            if (active && lane < LPG) {
-                float out[VEC];
+        if (active && slice == 0 && lane < LPG) {
+            float out[VEC];
 #pragma unroll
-                for (int j = 0; j < VEC; ++j) out[j] = squash(acc[j]);
-                store_vec_device_scope<VEC>(vres, ((uint32_t)row * (uint32_t)B + (uint32_t)c) * 4u, out);
-            }
-            // The tile must have reached device-scope visibility before the flag does: wait
-            // until every outstanding vector-memory operation of this wave has completed
-            // (s_waitcnt vmcnt(0); expcnt and lgkmcnt fields left at "no wait").
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-            __builtin_amdgcn_s_waitcnt(0x0F70);
-            if (lane == 0)
-                __hip_atomic_store(&ready[(size_t)(row - first_row) * (size_t)tiles + tile], 1, __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
+            for (int j = 0; j < VEC; ++j) out[j] = squash(acc[j]);
+            store_vec_device_scope<VEC>(vres, ((uint32_t)row * (uint32_t)B + (uint32_t)c) * 4u, out);
         }
     }
 }
@@ -541,9 +564,9 @@ struct DataflowArgs {
     const int32_t *unit_ptr;
     int first_unit, n_work, first_row;
     uint32_t v_bytes;
-    int *ready;
     DataflowCtl *ctl;
     int cus;
+    int units_per_level;     // average, for sizing the persistent grid
 };
 
 template <int VEC, int LPG, typename ACC>
@@ -557,12 +580,16 @@ int launch_dataflow(const LevelArgs &a, const DataflowArgs &d) {
                                                                   kMixedBlock, 0));
         per_cu = n > 0 ? n : 1;
     }
+    // Workgroups far ahead of the wavefront of finished rows only spin and re-read: a few levels'
+    // worth of units in flight is enough.
     long long blocks = (long long)d.cus * per_cu;
+    const long long useful = 2LL * d.units_per_level * tiles + 32;
+    if (blocks > useful) blocks = useful;
     if (blocks > d.n_work) blocks = d.n_work;
     if (blocks < 1) return ASNN_OK;
     hipLaunchKernelGGL((dataflow_kernel<VEC, LPG, ACC, kUnroll>), dim3((unsigned)blocks), dim3(kMixedBlock), 0, a.s,
                        a.row_ptr, a.col, a.w, a.V, d.v_bytes, a.B, d.unit_ptr, d.first_unit, d.n_work, tiles, d.first_row,
-                       d.ready, d.ctl);
+                       d.ctl);
     ASNN_HIP_TRY(hipGetLastError());
     return ASNN_OK;
 }
@@ -597,16 +624,15 @@ inline int tiles_for(int B) {
 
 struct ActivateWorkspace {
     DataflowCtl *ctl;
-    int *ready;
-    size_t n_flags, bytes;
+    size_t bytes;
 };
 
 inline ActivateWorkspace carve_activate(void *ws, int32_t n_nodes, int32_t B) {
+    (void)n_nodes;
+    (void)B;
     Carver c(ws);
     ActivateWorkspace w;
     w.ctl = c.take<DataflowCtl>(1);
-    w.n_flags = (size_t)n_nodes * (size_t)tiles_for(B);
-    w.ready = c.take<int>(w.n_flags + 1);
     w.bytes = c.off;
     return w;
 }
@@ -708,12 +734,13 @@ extern "C" int asnn_activate(const asnn_packed *packed, const int32_t *input_ids
             cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
         }
         ActivateWorkspace ws = carve_activate(workspace, n_nodes, B);
-        const size_t n_flags = (size_t)(n_nodes - first_row) * (size_t)tiles;
-        hipLaunchKernelGGL(dataflow_reset_kernel, dim3(blocks_for(n_flags, 256, 2048)), dim3(256), 0, s, ws.ready, n_flags,
-                           ws.ctl);
+        const size_t n_values = (size_t)(n_nodes - first_row) * (size_t)B;
+        hipLaunchKernelGGL(dataflow_reset_kernel, dim3(blocks_for(n_values, 256 * 8, 4096)), dim3(256), 0, s,
+                           reinterpret_cast<unsigned int *>(V + (size_t)first_row * (size_t)B), n_values, ws.ctl);
         ASNN_HIP_TRY(hipGetLastError());
+        const int units_per_level = (packed->n_units - packed->first_unit + n_levels - 2) / (n_levels - 1);
         DataflowArgs d{packed->unit_ptr, packed->first_unit, (int)n_work, first_row,
-                       (uint32_t)((uint64_t)n_nodes * (uint64_t)B * 4u), ws.ready, ws.ctl, cus};
+                       (uint32_t)((uint64_t)n_nodes * (uint64_t)B * 4u), ws.ctl, cus, units_per_level};
         ASNN_TRY(f32 ? launch_dataflow_any<float>(a, d) : launch_dataflow_any<double>(a, d));
     } else {
         for (int l = 1; l < n_levels; ++l) {
