@@ -46,6 +46,59 @@ def measured_traffic(config, flags):
     return None
 
 
+def paper_regime():
+    """The paper's own experiment on this machine: ONE input vector per activation, time against the
+    number of connections for shallow and deep networks, GPU (10 runs averaged, as in the paper's
+    experimental setup) against the sequential oracle (5 runs averaged).  Prints one JSON line per network."""
+    import numpy as np
+    import torch
+
+    import oracle
+    import paper_2005_04347_amd as amd
+    from workloads import layered_skip
+
+    amd.load()
+    for n_levels in (5, 40):
+        for n_edges in (1000, 2000, 4000, 8000, 16000, 30000, 70000, 150000, 300000):
+            n_nodes = max(n_edges // 10, 3 * n_levels)
+            n_io = max(4, n_nodes // 50)
+            wl = layered_skip(seed=1, n_nodes=n_nodes, n_inputs=n_io, n_outputs=n_io, n_levels=n_levels, B=1,
+                              mean_extra_degree=n_edges / (n_nodes - n_io) - 1.0)
+            net = amd.Network(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.output_ids)
+            X = torch.from_numpy(wl.X).cuda()
+            V = torch.empty((wl.n_nodes, 1), device="cuda")
+            Y = torch.empty((len(wl.output_ids), 1), device="cuda")
+            for _ in range(5):
+                net.activate(X, V=V, Y=Y)
+            torch.cuda.synchronize()
+            # resident: events around 10 activations; with transfers: host X in, host Y out, as the paper timed it
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(10):
+                net.activate(X, V=V, Y=Y)
+            e1.record()
+            torch.cuda.synchronize()
+            gpu_us = e0.elapsed_time(e1) * 1e3 / 10
+            t0 = time.perf_counter()
+            for _ in range(10):
+                Xd = torch.from_numpy(wl.X).cuda()
+                net.activate(Xd, V=V, Y=Y)
+                y_host = Y.cpu()
+            copy_us = (time.perf_counter() - t0) * 1e6 / 10
+            oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.X)
+            cpu_us = 0.0
+            for _ in range(5):          # the node loop only: the paper times activation after its preprocessing
+                tm = {}
+                ref = oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.X, timing=tm)
+                cpu_us += tm["activation_seconds"] * 1e6 / 5
+            err = float(np.abs(net.values_original_order(V).cpu().numpy().astype(np.float64) - ref).max())
+            print(json.dumps({"regime": "paper: batch 1", "connections": wl.n_edges, "nodes": wl.n_nodes,
+                              "levels": net.n_levels, "gpu_us_resident": round(gpu_us, 1),
+                              "gpu_us_with_host_copies": round(copy_us, 1), "cpu_oracle_us": round(cpu_us, 1),
+                              "speedup_resident": round(cpu_us / gpu_us, 2),
+                              "speedup_with_host_copies": round(cpu_us / copy_us, 2), "max_abs_err": err}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -55,8 +108,14 @@ def main():
     ap.add_argument("--flags", type=int, default=0, help="asnn_activate flags (2 = fp32 accumulate)")
     ap.add_argument("--schedule", choices=["auto", "levels", "dataflow"], default="auto",
                     help="level launches, persistent dataflow launch, or the library's own choice")
+    ap.add_argument("--graph", action="store_true", help="capture one asnn_activate in a HIP graph and time replays")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--paper-regime", action="store_true",
+                    help="batch-1 latency against connections, as in the paper's figures (prints one line per network)")
     args = ap.parse_args()
+    if args.paper_regime:
+        paper_regime()
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; samples and networks shard without any exchange "
               "(see DESIGN.md), but no multi-GPU figure is produced here. Use --gpus 1.", file=sys.stderr)
@@ -85,6 +144,18 @@ def main():
 
     def step():
         net.activate(X, V=V, Y=Y, flags=flags)
+
+    if args.graph:
+        net.workspace(B)
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            step()
+            side.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        torch.cuda.synchronize()
+        step = graph.replay
 
     for _ in range(args.warmup):
         step()
@@ -144,7 +215,7 @@ def main():
         "dtype": "f32" if (args.flags & 2) else "f64",
         "data": "synthetic",
         "config": {"workload": f"config{args.config}:{wl.name}", "n_nodes": wl.n_nodes, "n_edges": wl.n_edges,
-                   "n_levels": net.n_levels, "batch": B, "n_nets": wl.n_nets, "flags": flags, "schedule": args.schedule,
+                   "n_levels": net.n_levels, "batch": B, "n_nets": wl.n_nets, "flags": flags, "schedule": args.schedule, "hip_graph": bool(args.graph),
                    "preprocess_ms_first_call": round(prep_ms, 2)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,

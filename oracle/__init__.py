@@ -63,7 +63,7 @@ def _load():
         lib.asnn_oracle_activate.restype = ctypes.c_int
         lib.asnn_oracle_activate.argtypes = [ctypes.c_int32, ctypes.c_int64, i32p, i32p, f32p,
                                              ctypes.c_int32, i32p, f32p, ctypes.c_int32,
-                                             ctypes.c_int, ctypes.c_int, f32p]
+                                             ctypes.c_int, ctypes.c_int, f32p, ctypes.POINTER(ctypes.c_double)]
         _lib = lib
     return _lib
 
@@ -94,8 +94,9 @@ def levels(n_nodes, src, dst):
     return level[:n_nodes], int(nl.value)
 
 
-def activate(n_nodes, src, dst, w, input_ids, X, mode=F64, raw_inputs=False):
-    """-> val[float32 N, B] in ORIGINAL node ids: every node's activation."""
+def activate(n_nodes, src, dst, w, input_ids, X, mode=F64, raw_inputs=False, timing=None):
+    """-> val[float32 N, B] in ORIGINAL node ids: every node's activation.
+    timing: optional dict; receives {"activation_seconds": wall time of the node loop without the adjacency build}."""
     lib = _load()
     src, dst, w, input_ids = _i32(src), _i32(dst), _f32(w), _i32(input_ids)
     X = _f32(X)
@@ -104,10 +105,13 @@ def activate(n_nodes, src, dst, w, input_ids, X, mode=F64, raw_inputs=False):
     assert X.shape[0] == input_ids.shape[0]
     B = X.shape[1]
     val = np.full((max(n_nodes, 1), max(B, 1)), np.nan, dtype=np.float32)
+    seconds = ctypes.c_double(0.0)
     rc = lib.asnn_oracle_activate(n_nodes, src.shape[0], _p(src, ctypes.c_int32), _p(dst, ctypes.c_int32),
                                   _p(w, ctypes.c_float), input_ids.shape[0], _p(input_ids, ctypes.c_int32),
                                   _p(X, ctypes.c_float), B, int(mode), int(bool(raw_inputs)),
-                                  _p(val, ctypes.c_float))
+                                  _p(val, ctypes.c_float), ctypes.byref(seconds))
+    if timing is not None:
+        timing["activation_seconds"] = float(seconds.value)
     if rc:
         raise OracleError(rc)
     return val[:n_nodes, :B]

@@ -37,10 +37,12 @@
  * set-based segmentation written out in oracle/segment_network.py, dense
  * matmul chains for unpruned layered nets, metamorphic relabelling.
  */
+#define _POSIX_C_SOURCE 199309L   /* clock_gettime under -std=c11 */
 #include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+#include <time.h>
 
 #define ASNN_ORACLE_OK 0
 #define ASNN_ORACLE_ERR_INDEX -1
@@ -135,10 +137,19 @@ static float squash_f32(float s) { return 1.0f / (1.0f + expf(-4.97f * s)); }
 /* Full activation.  val[n*B] (node-major, batch contiguous, ORIGINAL node
  * ids) receives the activation of every node for every input vector.
  * X[n_inputs*B]: row k feeds input_ids[k].  raw_inputs != 0 stores the input
- * values unsquashed (an option outside the paper, which squashes sensors). */
+ * values unsquashed (an option outside the paper, which squashes sensors).
+ * activation_seconds (may be NULL) receives the wall time of the node loop
+ * alone, i.e. without building the adjacency lists (the paper times its
+ * sequential activation after its preprocessing step). */
+static double now_seconds(void) {
+    struct timespec ts;
+    clock_gettime(CLOCK_MONOTONIC, &ts);
+    return (double)ts.tv_sec + 1e-9 * (double)ts.tv_nsec;
+}
+
 int asnn_oracle_activate(int32_t n, int64_t e, const int32_t *src, const int32_t *dst, const float *w,
                          int32_t n_inputs, const int32_t *input_ids, const float *X, int32_t B,
-                         int mode, int raw_inputs, float *val) {
+                         int mode, int raw_inputs, float *val, double *activation_seconds) {
     adjacency a;
     int rc = adjacency_build(&a, n, e, src, dst);
     if (rc) return rc;
@@ -156,6 +167,7 @@ int asnn_oracle_activate(int32_t n, int64_t e, const int32_t *src, const int32_t
         slot[v] = k;
     }
     int32_t head = 0, tail = 0;
+    const double t_start = now_seconds();
     for (int32_t v = 0; v < n; ++v)
         if (a.indeg[v] == 0) queue[tail++] = v;
     while (head < tail) {
@@ -189,6 +201,7 @@ int asnn_oracle_activate(int32_t n, int64_t e, const int32_t *src, const int32_t
             if (--a.indeg[u] == 0) queue[tail++] = u;
         }
     }
+    if (activation_seconds) *activation_seconds = now_seconds() - t_start;
     if (tail < n) rc = ASNN_ORACLE_ERR_CYCLE;
 done:
     free(slot); free(queue); free(acc64); free(acc32);

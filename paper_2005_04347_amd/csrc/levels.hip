@@ -16,7 +16,7 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kSweepsPerSync = 64;     // frontier sweeps enqueued between two host reads
 constexpr int kGroup = 16;             // lanes that share one frontier node's out-edges
-constexpr unsigned kSweepBlocks = 2048;
+constexpr unsigned kSweepBlocks = 512;
 
 // Slots of the small control block in device memory.
 enum Ctl : int {
@@ -28,6 +28,21 @@ enum Ctl : int {
 };
 
 __device__ inline void flag_error(int *ctl, int code) { atomicCAS(&ctl[kErr], 0, code); }
+
+// Appends `node` to list[] for every active lane with `has` set, with one atomic
+// on *count per wavefront instead of one per lane (thousands of lanes adding
+// to one address serialise).  May be called from divergent code.
+__device__ inline void wave_append(bool has, int32_t node, int32_t *__restrict__ list, int *count) {
+    const unsigned long long mask = __ballot(has);
+    if (mask == 0) return;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int leader = __ffsll((long long)mask) - 1;
+    int base = 0;
+    if (lane == leader) base = atomicAdd(count, __popcll(mask));
+    base = __shfl(base, leader, kWave);
+    const unsigned long long below = (lane == 0) ? 0ull : (~0ull >> (kWave - lane));
+    if (has) list[base + __popcll(mask & below)] = node;
+}
 
 __global__ void degree_kernel(const int32_t *__restrict__ src, const int32_t *__restrict__ dst, int64_t n_edges,
                               int32_t n_nodes, int32_t *indeg, int32_t *outdeg, int *ctl) {
@@ -69,13 +84,9 @@ __global__ void fill_out_kernel(const int32_t *__restrict__ src, const int32_t *
 __global__ void first_frontier_kernel(int32_t n_nodes, const int32_t *__restrict__ indeg, int32_t *__restrict__ level,
                                       int32_t *__restrict__ frontier, int *ctl) {
     const int v = blockIdx.x * blockDim.x + threadIdx.x;
-    if (v >= n_nodes) return;
-    if (indeg[v] == 0) {
-        level[v] = 0;
-        frontier[atomicAdd(&ctl[kCount0], 1)] = v;
-    } else {
-        level[v] = -1;
-    }
+    const bool root = v < n_nodes && indeg[v] == 0;
+    if (v < n_nodes) level[v] = root ? 0 : -1;
+    wave_append(root, v, frontier, &ctl[kCount0]);
 }
 
 // One sweep: every node of frontier k releases its out-edges; a destination
@@ -104,10 +115,9 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(int k, const int32_t *_
         const int32_t e1 = out_ptr[v + 1];
         for (int32_t e = out_ptr[v] + sub; e < e1; e += kGroup) {
             const int32_t u = out_dst[e];
-            if (atomicSub(&indeg[u], 1) == 1) {
-                level[u] = k + 1;
-                frontier_out[atomicAdd(count_out, 1)] = u;
-            }
+            const bool last = atomicSub(&indeg[u], 1) == 1;
+            if (last) level[u] = k + 1;
+            wave_append(last, u, frontier_out, count_out);
         }
     }
 }

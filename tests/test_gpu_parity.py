@@ -308,3 +308,44 @@ def test_full_size_configs(amd, idx):
         # nothing outside the sampled columns is left unwritten
         assert not torch.isnan(V).any()
         del V, Y
+
+
+def test_graph_capture_replays_match_eager(amd):
+    """asnn_activate enqueues kernels only (no memset, no allocation, no host
+    synchronisation), so a stream capture of it replays correctly: several
+    replays, with eager work and synchronisations between them, all equal the
+    eager result, for both schedules."""
+    wl = make_config(3, "small")
+    net = amd.Network(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.output_ids)
+    X = torch.from_numpy(wl.X).cuda()
+    want_V, want_Y = net.activate(X, flags=LEVELS)
+    torch.cuda.synchronize()
+    for sched in (LEVELS, DATAFLOW):
+        V = torch.zeros_like(want_V)
+        Y = torch.zeros_like(want_Y)
+        net.workspace(wl.B)                       # allocate outside the capture
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            net.activate(X, V=V, Y=Y, flags=sched)           # warm-up on the capture stream
+            side.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                net.activate(X, V=V, Y=Y, flags=sched)
+        torch.cuda.synchronize()
+        for rep in range(3):
+            V.fill_(float("nan"))
+            Y.fill_(float("nan"))
+            X2 = X * 0.5 if rep == 1 else X           # replay reads X in place: change and restore it
+            if rep == 1:
+                X.copy_(X2)
+            graph.replay()
+            torch.cuda.synchronize()
+            if rep == 1:
+                ref_V, ref_Y = net.activate(X2.contiguous(), flags=LEVELS)
+                torch.cuda.synchronize()
+                assert torch.equal(V, ref_V) and torch.equal(Y, ref_Y)
+                X.copy_(torch.from_numpy(wl.X).cuda())
+            else:
+                assert torch.equal(V, want_V) and torch.equal(Y, want_Y), (sched, rep)
+            net.activate(X, flags=sched)              # eager work between replays
+            net.check(wl.B)
