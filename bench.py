@@ -199,7 +199,9 @@ def main():
     value = edge_samples / (wall_ms * 1e-3) / 1e9
     alg_bytes = algorithmic_bytes(wl.n_nodes, wl.n_edges, len(wl.input_ids), B)
     achieved = alg_bytes / (dev_ms_med * 1e-3) / 1e9
-    launches = max(net.n_levels - 1, 1)          # one gather launch per level above the input level
+    taken = amd.asnn_activate_schedule(net.graph, B, True, flags)
+    # level launches: one gather launch per level above the input level; dataflow: one persistent launch
+    launches = 1 if taken == "dataflow" else max(net.n_levels - 1, 1)
     traffic = measured_traffic(args.config, args.flags)
     out = {
         "metric": "G edge*samples/s for full ASNN activation",
@@ -215,11 +217,12 @@ def main():
         "dtype": "f32" if (args.flags & 2) else "f64",
         "data": "synthetic",
         "config": {"workload": f"config{args.config}:{wl.name}", "n_nodes": wl.n_nodes, "n_edges": wl.n_edges,
-                   "n_levels": net.n_levels, "batch": B, "n_nets": wl.n_nets, "flags": flags, "schedule": args.schedule, "hip_graph": bool(args.graph),
+                   "n_levels": net.n_levels, "batch": B, "n_nets": wl.n_nets, "flags": flags, "schedule": args.schedule, "schedule_taken": taken, "hip_graph": bool(args.graph),
                    "preprocess_ms_first_call": round(prep_ms, 2)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
-                     "kernel": "gather_light_kernel / gather_mixed_kernel (one launch per level)",
+                     "kernel": ("dataflow_kernel (one persistent launch)" if taken == "dataflow" else
+                                "gather_light_kernel / gather_mixed_kernel (one launch per level)"),
                      "launches_per_step": launches,
                      "algorithmic_bytes_per_launch": alg_bytes / launches,
                      "avg_launch_us": round(dev_ms_med * 1e3 / launches, 3),

@@ -163,6 +163,10 @@ int asnn_pack_csr(const int32_t *src, const int32_t *dst, const float *w, const 
  * a valid packed record) stops waiting and raises a flag in the workspace
  * that asnn_activate_status reports. */
 size_t asnn_activate_workspace_bytes(int32_t n_nodes, int32_t B);
+/* Which schedule asnn_activate takes for this record, batch width, workspace
+ * (given or not) and flags: 0 = one launch per level, 1 = dataflow, < 0 = the
+ * error asnn_activate would return for this choice.  Launches nothing. */
+int asnn_activate_schedule(const asnn_packed *packed, int32_t B, int has_workspace, uint32_t flags);
 int asnn_activate(const asnn_packed *packed,
                   const int32_t *input_ids, int32_t n_inputs,
                   const int32_t *output_ids, int32_t n_outputs,

@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     Network,
     PackedGraph,
     asnn_activate,
+    asnn_activate_schedule,
     asnn_activate_status,
     asnn_activate_workspace,
     asnn_build_levels,

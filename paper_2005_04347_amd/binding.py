@@ -35,7 +35,7 @@ EXPORTS = [
     "asnn_strerror", "asnn_last_hip_error", "asnn_version",
     "asnn_levels_workspace_bytes", "asnn_build_levels",
     "asnn_pack_workspace_bytes", "asnn_pack_csr", "asnn_activate_workspace_bytes", "asnn_activate",
-    "asnn_activate_status", "asnn_device_copy",
+    "asnn_activate_status", "asnn_activate_schedule", "asnn_device_copy",
 ]
 
 
@@ -79,6 +79,8 @@ def load() -> ctypes.CDLL:
     lib.asnn_activate_workspace_bytes.argtypes = [i32, i32]
     lib.asnn_activate.restype = ctypes.c_int
     lib.asnn_activate.argtypes = [ctypes.POINTER(AsnnPacked), vp, i32, vp, i32, vp, i32, vp, vp, vp, sz, u32, vp]
+    lib.asnn_activate_schedule.restype = ctypes.c_int
+    lib.asnn_activate_schedule.argtypes = [ctypes.POINTER(AsnnPacked), i32, ctypes.c_int, u32]
     lib.asnn_activate_status.restype = ctypes.c_int
     lib.asnn_activate_status.argtypes = [vp, vp]
     lib.asnn_device_copy.restype = ctypes.c_int
@@ -214,6 +216,15 @@ def asnn_activate(g: PackedGraph, input_ids: torch.Tensor, X: torch.Tensor,
     if rc != 0:
         raise AsnnError(rc, "asnn_activate")
     return V, Y
+
+
+def asnn_activate_schedule(g: PackedGraph, B: int, has_workspace: bool = True, flags: int = 0) -> str:
+    """'levels' or 'dataflow': the schedule asnn_activate would take."""
+    lib = load()
+    rc = lib.asnn_activate_schedule(ctypes.byref(g.record), B, int(has_workspace), flags)
+    if rc < 0:
+        raise AsnnError(rc, "asnn_activate_schedule")
+    return "dataflow" if rc == 1 else "levels"
 
 
 def asnn_activate_status(workspace: Optional[torch.Tensor]) -> None:

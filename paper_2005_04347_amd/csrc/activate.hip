@@ -637,6 +637,9 @@ inline ActivateWorkspace carve_activate(void *ws, int32_t n_nodes, int32_t B) {
     return w;
 }
 
+// Which schedule an activation takes: 0 = one launch per level, 1 = dataflow, < 0 = error.
+int choose_schedule(const asnn_packed *packed, int32_t B, bool has_workspace, uint32_t flags);
+
 // Average connections*samples per level below which the persistent dataflow
 // launch beats one launch per level (measured on MI355X: a level launch costs
 // about 8 us however little it does).
@@ -646,6 +649,33 @@ constexpr double kDataflowMaxLevelWork = 8.0e6;
 }  // namespace asnn
 
 using namespace asnn;
+
+namespace asnn {
+namespace {
+int choose_schedule(const asnn_packed *packed, int32_t B, bool has_workspace, uint32_t flags) {
+    const int32_t n_nodes = packed->n_nodes, n_levels = packed->n_levels;
+    if ((flags & ASNN_FLAG_LEVEL_LAUNCHES) && (flags & ASNN_FLAG_DATAFLOW)) return ASNN_ERR_SIZE;
+    const long long n_work = (long long)(packed->n_units - packed->first_unit) * tiles_for(B);
+    const bool possible = has_workspace && packed->unit_ptr && n_levels > 1 && packed->n_units > 0 &&
+                          packed->first_unit >= 0 && packed->first_unit <= packed->n_units &&
+                          packed->n_units <= n_nodes && n_work > 0 && n_work < 0x7fffffffLL &&
+                          (uint64_t)n_nodes * (uint64_t)B * 4u <= 0xffffffffull;
+    if (flags & ASNN_FLAG_DATAFLOW) {
+        if (!has_workspace) return ASNN_ERR_NULL;
+        if (!possible && n_levels > 1) return ASNN_ERR_SIZE;
+        return possible ? 1 : 0;
+    }
+    if ((flags & ASNN_FLAG_LEVEL_LAUNCHES) || !possible) return 0;
+    return (double)packed->n_edges * (double)B / (double)(n_levels - 1) < kDataflowMaxLevelWork ? 1 : 0;
+}
+}  // namespace
+}  // namespace asnn
+
+extern "C" int asnn_activate_schedule(const asnn_packed *packed, int32_t B, int has_workspace, uint32_t flags) {
+    if (!packed) return ASNN_ERR_NULL;
+    if (packed->n_nodes <= 0 || packed->n_levels <= 0 || packed->n_edges < 0 || B <= 0) return ASNN_ERR_SIZE;
+    return choose_schedule(packed, B, has_workspace != 0, flags);
+}
 
 extern "C" size_t asnn_activate_workspace_bytes(int32_t n_nodes, int32_t B) {
     if (n_nodes <= 0 || B <= 0) return 0;
@@ -681,24 +711,12 @@ extern "C" int asnn_activate(const asnn_packed *packed, const int32_t *input_ids
     if (level_ptr_host[0] != 0 || level_ptr_host[n_keys] != n_nodes) return ASNN_ERR_SIZE;
     for (int k = 0; k < n_keys; ++k)
         if (level_ptr_host[k] > level_ptr_host[k + 1]) return ASNN_ERR_SIZE;
-    if ((flags & ASNN_FLAG_LEVEL_LAUNCHES) && (flags & ASNN_FLAG_DATAFLOW)) return ASNN_ERR_SIZE;
-
-    // schedule
+    const int plan = choose_schedule(packed, B, workspace != nullptr, flags);
+    if (plan < 0) return plan;
+    const bool dataflow = plan == 1;
     const int tiles = tiles_for(B);
     const int first_row = n_levels > 1 ? level_ptr_host[ASNN_CLASSES] : n_nodes;
     const long long n_work = (long long)(packed->n_units - packed->first_unit) * tiles;
-    const bool dataflow_possible = workspace && packed->unit_ptr && n_levels > 1 && packed->n_units > 0 &&
-                                   packed->first_unit >= 0 && packed->first_unit <= packed->n_units &&
-                                   packed->n_units <= n_nodes && n_work > 0 && n_work < 0x7fffffffLL &&
-                                   (uint64_t)n_nodes * (uint64_t)B * 4u <= 0xffffffffull;
-    bool dataflow = false;
-    if (flags & ASNN_FLAG_DATAFLOW) {
-        if (!workspace) return ASNN_ERR_NULL;
-        if (!dataflow_possible && n_levels > 1) return ASNN_ERR_SIZE;
-        dataflow = dataflow_possible;
-    } else if (!(flags & ASNN_FLAG_LEVEL_LAUNCHES) && dataflow_possible) {
-        dataflow = (double)n_edges * (double)B / (double)(n_levels - 1) < kDataflowMaxLevelWork;
-    }
     if (dataflow && (((uintptr_t)workspace & 255u) != 0 || workspace_bytes < asnn_activate_workspace_bytes(n_nodes, B)))
         return ASNN_ERR_WORKSPACE;
 
