@@ -349,3 +349,46 @@ def test_graph_capture_replays_match_eager(amd):
                 assert torch.equal(V, want_V) and torch.equal(Y, want_Y), (sched, rep)
             net.activate(X, flags=sched)              # eager work between replays
             net.check(wl.B)
+
+
+def test_dataflow_wait_is_bounded_and_reported(amd):
+    """Failure handling of the persistent schedule, forced from the host: a
+    packed record whose first unit above level 0 is skipped leaves rows that
+    nobody writes.  Their consumers must give up after the time limit, every
+    wave must still exit, and asnn_activate_status must report the timeout.
+    The next, valid activation on the same workspace is clean again."""
+    import copy
+    import ctypes
+    import time
+    wl = make_config(3, "small")
+    net = amd.Network(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.output_ids)
+    good_V, _ = net.activate(wl.X, flags=DATAFLOW)
+    net.check(wl.B)
+    g = net.graph
+    broken = copy.copy(g)
+    rec = type(g.record)()
+    ctypes.pointer(rec)[0] = g.record
+    rec.first_unit = g.first_unit + 1
+    broken.record = rec
+    X = torch.from_numpy(wl.X).cuda()
+    t0 = time.time()
+    amd.asnn_activate(broken, net.input_ids, X, net.output_ids, flags=DATAFLOW, workspace=net.workspace(wl.B))
+    with pytest.raises(amd.AsnnError) as e:
+        amd.asnn_activate_status(net.workspace(wl.B))
+    assert e.value.code == -11
+    assert time.time() - t0 < 30
+    V, _ = net.activate(wl.X, flags=DATAFLOW)
+    net.check(wl.B)
+    assert torch.equal(V, good_V)
+
+
+def test_schedule_choice_is_reported(amd):
+    wl = make_config(3, "small")
+    net = amd.Network(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.output_ids)
+    g = net.graph
+    assert amd.asnn_activate_schedule(g, wl.B, True, 0) == "dataflow"       # small levels
+    assert amd.asnn_activate_schedule(g, wl.B, False, 0) == "levels"        # no workspace
+    assert amd.asnn_activate_schedule(g, wl.B, True, LEVELS) == "levels"
+    assert amd.asnn_activate_schedule(g, 1 << 20, True, 0) == "levels"      # big levels
+    with pytest.raises(amd.AsnnError):
+        amd.asnn_activate_schedule(g, wl.B, False, DATAFLOW)
