@@ -94,6 +94,33 @@ int asnn_build_levels(int32_t n_nodes, int64_t n_edges,
                       int32_t *level_out, int32_t *n_levels_out,
                       void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- 1b. required set (optional) -----------------------------------------
+ * The segmentation algorithm only layers "required" nodes: those needed to
+ * compute the outputs (its argument R).  asnn_required_set marks every node
+ * from which an output can be reached (outputs included); asnn_filter_required
+ * drops the connections that end in a node outside R, keeping the order of the
+ * others.  Running asnn_build_levels / asnn_pack_csr / asnn_activate on the
+ * kept connections (same n_nodes) gives bit-identical activations for every
+ * node of R; nodes outside R become isolated level-0 rows whose value is not
+ * meaningful, and no connection work is spent on them.
+ *   output_ids     device int32[n_outputs]
+ *   required_out   device int32[n_nodes]   1 = in R, 0 = not
+ *   n_required_out host   int32*           |R|
+ *   src_out, dst_out, w_out  device, n_edges entries each (n_kept_out of them used)
+ *   n_kept_out     host   int64*
+ *   workspaces     device, >= the matching *_workspace_bytes(), 256-byte aligned
+ * Errors: NULL, SIZE, INDEX, WORKSPACE, HIP.  Both block until the host values are known. */
+size_t asnn_required_workspace_bytes(int32_t n_nodes, int64_t n_edges);
+int asnn_required_set(int32_t n_nodes, int64_t n_edges, const int32_t *src, const int32_t *dst,
+                      const int32_t *output_ids, int32_t n_outputs,
+                      int32_t *required_out, int32_t *n_required_out,
+                      void *workspace, size_t workspace_bytes, void *stream);
+size_t asnn_filter_workspace_bytes(int64_t n_edges);
+int asnn_filter_required(int32_t n_nodes, int64_t n_edges, const int32_t *src, const int32_t *dst, const float *w,
+                         const int32_t *required,
+                         int32_t *src_out, int32_t *dst_out, float *w_out, int64_t *n_kept_out,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
 /* ---- 2. pack -----------------------------------------------------------
  * Level-contiguous, destination-sorted CSR (replaces the paper's per-node
  * record with its inNodes / inWeights arrays and the array sorted by layer).

@@ -64,6 +64,8 @@ def _load():
         lib.asnn_oracle_activate.argtypes = [ctypes.c_int32, ctypes.c_int64, i32p, i32p, f32p,
                                              ctypes.c_int32, i32p, f32p, ctypes.c_int32,
                                              ctypes.c_int, ctypes.c_int, f32p, ctypes.POINTER(ctypes.c_double)]
+        lib.asnn_oracle_required.restype = ctypes.c_int
+        lib.asnn_oracle_required.argtypes = [ctypes.c_int32, ctypes.c_int64, i32p, i32p, ctypes.c_int32, i32p, i32p]
         _lib = lib
     return _lib
 
@@ -115,3 +117,15 @@ def activate(n_nodes, src, dst, w, input_ids, X, mode=F64, raw_inputs=False, tim
     if rc:
         raise OracleError(rc)
     return val[:n_nodes, :B]
+
+
+def required(n_nodes, src, dst, output_ids):
+    """-> bool[N]: the segmentation algorithm's set R (nodes from which an output is reachable, outputs included)."""
+    lib = _load()
+    src, dst, output_ids = _i32(src), _i32(dst), _i32(output_ids)
+    mask = np.zeros(max(n_nodes, 1), dtype=np.int32)
+    rc = lib.asnn_oracle_required(n_nodes, src.shape[0], _p(src, ctypes.c_int32), _p(dst, ctypes.c_int32),
+                                  output_ids.shape[0], _p(output_ids, ctypes.c_int32), _p(mask, ctypes.c_int32))
+    if rc:
+        raise OracleError(rc)
+    return mask[:n_nodes].astype(bool)

@@ -131,6 +131,36 @@ int asnn_oracle_levels(int32_t n, int64_t e, const int32_t *src, const int32_t *
     return ASNN_ORACLE_OK;
 }
 
+/* Required set R of the segmentation algorithm (its first argument: the nodes
+ * needed to compute the outputs): required[v] = 1 iff some output can be
+ * reached from v along connections, outputs included.  Plain reverse
+ * traversal from the outputs with an explicit stack. */
+int asnn_oracle_required(int32_t n, int64_t e, const int32_t *src, const int32_t *dst,
+                         int32_t n_outputs, const int32_t *output_ids, int32_t *required) {
+    adjacency a;
+    int rc = adjacency_build(&a, n, e, src, dst);
+    if (rc) return rc;
+    int32_t *stack = malloc(sizeof(int32_t) * ((size_t)n + 1));
+    if (!stack) { adjacency_free(&a); return ASNN_ORACLE_ERR_ALLOC; }
+    int32_t top = 0;
+    for (int32_t v = 0; v < n; ++v) required[v] = 0;
+    for (int32_t k = 0; k < n_outputs; ++k) {
+        int32_t v = output_ids[k];
+        if (v < 0 || v >= n) { free(stack); adjacency_free(&a); return ASNN_ORACLE_ERR_INDEX; }
+        if (!required[v]) { required[v] = 1; stack[top++] = v; }
+    }
+    while (top > 0) {
+        int32_t v = stack[--top];
+        for (int64_t k = a.in_ptr[v]; k < a.in_ptr[v + 1]; ++k) {
+            int32_t u = src[a.in_edge[k]];
+            if (!required[u]) { required[u] = 1; stack[top++] = u; }
+        }
+    }
+    free(stack);
+    adjacency_free(&a);
+    return ASNN_ORACLE_OK;
+}
+
 static float squash_f64(double s) { return (float)(1.0 / (1.0 + exp(-SLOPE * s))); }
 static float squash_f32(float s) { return 1.0f / (1.0f + expf(-4.97f * s)); }
 

@@ -34,6 +34,7 @@ ERR_NAMES = {
 EXPORTS = [
     "asnn_strerror", "asnn_last_hip_error", "asnn_version",
     "asnn_levels_workspace_bytes", "asnn_build_levels",
+    "asnn_required_workspace_bytes", "asnn_required_set", "asnn_filter_workspace_bytes", "asnn_filter_required",
     "asnn_pack_workspace_bytes", "asnn_pack_csr", "asnn_activate_workspace_bytes", "asnn_activate",
     "asnn_activate_status", "asnn_activate_schedule", "asnn_device_copy",
 ]
@@ -71,6 +72,14 @@ def load() -> ctypes.CDLL:
     lib.asnn_levels_workspace_bytes.argtypes = [i32, i64]
     lib.asnn_build_levels.restype = ctypes.c_int
     lib.asnn_build_levels.argtypes = [i32, i64, vp, vp, vp, i32, vp, ctypes.POINTER(i32), vp, sz, vp]
+    lib.asnn_required_workspace_bytes.restype = sz
+    lib.asnn_required_workspace_bytes.argtypes = [i32, i64]
+    lib.asnn_required_set.restype = ctypes.c_int
+    lib.asnn_required_set.argtypes = [i32, i64, vp, vp, vp, i32, vp, ctypes.POINTER(i32), vp, sz, vp]
+    lib.asnn_filter_workspace_bytes.restype = sz
+    lib.asnn_filter_workspace_bytes.argtypes = [i64]
+    lib.asnn_filter_required.restype = ctypes.c_int
+    lib.asnn_filter_required.argtypes = [i32, i64, vp, vp, vp, vp, vp, vp, vp, ctypes.POINTER(i64), vp, sz, vp]
     lib.asnn_pack_workspace_bytes.restype = sz
     lib.asnn_pack_workspace_bytes.argtypes = [i32, i64]
     lib.asnn_pack_csr.restype = ctypes.c_int
@@ -129,6 +138,42 @@ def asnn_build_levels(n_nodes: int, src: torch.Tensor, dst: torch.Tensor, input_
     if rc != 0:
         raise AsnnError(rc, "asnn_build_levels")
     return level[:n_nodes], int(n_levels.value)
+
+
+def asnn_required_set(n_nodes: int, src: torch.Tensor, dst: torch.Tensor, output_ids: torch.Tensor):
+    """-> (required: int32 device tensor [n_nodes] of 0/1, n_required: int)."""
+    lib = load()
+    device = src.device
+    n_edges = int(src.numel())
+    required = torch.empty(max(n_nodes, 1), dtype=torch.int32, device=device)
+    ws = _workspace(lib.asnn_required_workspace_bytes(n_nodes, n_edges), device)
+    count = ctypes.c_int32(-1)
+    rc = lib.asnn_required_set(n_nodes, n_edges, _ptr(src), _ptr(dst), _ptr(output_ids), int(output_ids.numel()),
+                               ctypes.c_void_p(required.data_ptr()), ctypes.byref(count),
+                               ctypes.c_void_p(ws.data_ptr()), ws.numel(), _stream())
+    if rc != 0:
+        raise AsnnError(rc, "asnn_required_set")
+    return required[:n_nodes], int(count.value)
+
+
+def asnn_filter_required(n_nodes: int, src, dst, w, required):
+    """-> (src, dst, w) of the connections that end in a required node, order kept."""
+    lib = load()
+    device = src.device
+    n_edges = int(src.numel())
+    so = torch.empty(max(n_edges, 1), dtype=torch.int32, device=device)
+    do = torch.empty(max(n_edges, 1), dtype=torch.int32, device=device)
+    wo = torch.empty(max(n_edges, 1), dtype=torch.float32, device=device)
+    ws = _workspace(lib.asnn_filter_workspace_bytes(n_edges), device)
+    kept = ctypes.c_int64(-1)
+    rc = lib.asnn_filter_required(n_nodes, n_edges, _ptr(src), _ptr(dst), _ptr(w), _ptr(required),
+                                  ctypes.c_void_p(so.data_ptr()), ctypes.c_void_p(do.data_ptr()),
+                                  ctypes.c_void_p(wo.data_ptr()), ctypes.byref(kept),
+                                  ctypes.c_void_p(ws.data_ptr()), ws.numel(), _stream())
+    if rc != 0:
+        raise AsnnError(rc, "asnn_filter_required")
+    k = int(kept.value)
+    return so[:k], do[:k], wo[:k]
 
 
 class AsnnPacked(ctypes.Structure):
@@ -248,7 +293,7 @@ def asnn_device_copy(dst: torch.Tensor, src: torch.Tensor):
 class Network:
     """Convenience wrapper: build levels + pack once, activate many times."""
 
-    def __init__(self, n_nodes, src, dst, w, input_ids, output_ids, device="cuda:0"):
+    def __init__(self, n_nodes, src, dst, w, input_ids, output_ids, device="cuda:0", required_only=False):
         self.device = torch.device(device)
         self.n_nodes = int(n_nodes)
         self.src = _dev_i32(src, self.device)
@@ -256,7 +301,12 @@ class Network:
         self.w_edges = _dev_f32(w, self.device)
         self.input_ids = _dev_i32(input_ids, self.device)
         self.output_ids = _dev_i32(output_ids, self.device)
+        self.required = None
         with torch.cuda.device(self.device):
+            if required_only:       # keep only the connections the outputs depend on
+                self.required, self.n_required = asnn_required_set(self.n_nodes, self.src, self.dst, self.output_ids)
+                self.src, self.dst, self.w_edges = asnn_filter_required(self.n_nodes, self.src, self.dst, self.w_edges,
+                                                                        self.required)
             self.level, self.n_levels = asnn_build_levels(self.n_nodes, self.src, self.dst, self.input_ids)
             self.graph = asnn_pack_csr(self.n_nodes, self.n_levels, self.src, self.dst, self.w_edges, self.level)
 

@@ -218,3 +218,184 @@ extern "C" int asnn_build_levels(int32_t n_nodes, int64_t n_edges, const int32_t
     *n_levels_out = host_ctl[kLevels];
     return ASNN_OK;
 }
+
+// ------------------------------------------------------------ required set
+// The segmentation algorithm only layers nodes of the "required" set R: the
+// nodes needed to compute the outputs.  R is what reaches an output, found by
+// the same frontier sweep on the transposed graph (out-adjacency of (dst, src)
+// = incoming connections grouped by node), started from the outputs.
+namespace asnn {
+namespace {
+
+__global__ void seed_outputs_kernel(const int32_t *__restrict__ output_ids, int32_t n_outputs, int32_t n_nodes,
+                                    int32_t *required, int32_t *__restrict__ frontier, int *ctl) {
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    bool first = false;
+    int32_t v = 0;
+    if (k < n_outputs) {
+        v = output_ids[k];
+        if (v < 0 || v >= n_nodes) flag_error(ctl, ASNN_ERR_INDEX);
+        else first = atomicExch(&required[v], 1) == 0;          // an id listed twice is seeded once
+    }
+    wave_append(first, v, frontier, &ctl[kCount0]);
+}
+
+__global__ __launch_bounds__(kThreads) void reach_sweep_kernel(int k, const int32_t *__restrict__ in_ptr,
+                                                                const int32_t *__restrict__ in_src, int32_t *required,
+                                                                const int32_t *__restrict__ frontier_in,
+                                                                int32_t *__restrict__ frontier_out, int *ctl) {
+    const int count = ctl[kCount0 + k % 3];
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        ctl[kCount0 + (k + 2) % 3] = 0;
+        if (count > 0) atomicAdd(&ctl[kAssigned], count);
+    }
+    if (count == 0) return;
+    int *count_out = &ctl[kCount0 + (k + 1) % 3];
+    const int sub = threadIdx.x % kGroup;
+    const int groups = gridDim.x * (kThreads / kGroup);
+    for (int f = blockIdx.x * (kThreads / kGroup) + threadIdx.x / kGroup; f < count; f += groups) {
+        const int32_t v = frontier_in[f];
+        const int32_t e1 = in_ptr[v + 1];
+        for (int32_t e = in_ptr[v] + sub; e < e1; e += kGroup) {
+            const int32_t a = in_src[e];
+            const bool first = atomicExch(&required[a], 1) == 0;
+            wave_append(first, a, frontier_out, count_out);
+        }
+    }
+}
+
+__global__ void keep_flag_kernel(const int32_t *__restrict__ src, const int32_t *__restrict__ dst,
+                                 const int32_t *__restrict__ required, int64_t n_edges, int32_t n_nodes,
+                                 int32_t *__restrict__ keep, int *err) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e <= n_edges; e += stride) {
+        if (e == n_edges) { keep[e] = 0; continue; }
+        const int32_t a = src[e], b = dst[e];
+        if (a < 0 || a >= n_nodes || b < 0 || b >= n_nodes) { atomicCAS(err, 0, ASNN_ERR_INDEX); keep[e] = 0; continue; }
+        keep[e] = required[b] != 0 ? 1 : 0;
+    }
+}
+
+__global__ void compact_edges_kernel(const int32_t *__restrict__ src, const int32_t *__restrict__ dst,
+                                     const float *__restrict__ w, const int32_t *__restrict__ pos, int64_t n_edges,
+                                     int32_t *__restrict__ src_out, int32_t *__restrict__ dst_out,
+                                     float *__restrict__ w_out) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n_edges; e += stride) {
+        const int32_t p = pos[e];
+        if (pos[e + 1] != p) {          // kept: exclusive scan of the keep flags gives its slot
+            src_out[p] = src[e];
+            dst_out[p] = dst[e];
+            w_out[p] = w[e];
+        }
+    }
+}
+
+struct FilterWorkspace {
+    int *err;
+    int32_t *pos, *scan_tmp;
+    size_t bytes;
+};
+
+FilterWorkspace carve_filter(void *ws, int64_t n_edges) {
+    Carver c(ws);
+    FilterWorkspace w;
+    const size_t e = (size_t)n_edges;
+    w.err = c.take<int>(64);
+    w.pos = c.take<int32_t>(e + 2);
+    w.scan_tmp = c.take<int32_t>(scan_tmp_ints(e + 1));
+    w.bytes = c.off;
+    return w;
+}
+
+}  // namespace
+}  // namespace asnn
+
+extern "C" size_t asnn_required_workspace_bytes(int32_t n_nodes, int64_t n_edges) {
+    return asnn_levels_workspace_bytes(n_nodes, n_edges);
+}
+
+extern "C" int asnn_required_set(int32_t n_nodes, int64_t n_edges, const int32_t *src, const int32_t *dst,
+                                 const int32_t *output_ids, int32_t n_outputs, int32_t *required_out,
+                                 int32_t *n_required_out, void *workspace, size_t workspace_bytes, void *stream) {
+    if (n_nodes <= 0 || n_edges < 0 || n_edges >= (int64_t)INT32_MAX || n_outputs < 0) return ASNN_ERR_SIZE;
+    if (!required_out || !n_required_out || !workspace) return ASNN_ERR_NULL;
+    if ((n_edges > 0 && (!src || !dst)) || (n_outputs > 0 && !output_ids)) return ASNN_ERR_NULL;
+    if (((uintptr_t)workspace & 255u) != 0 || workspace_bytes < asnn_required_workspace_bytes(n_nodes, n_edges))
+        return ASNN_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    LevelsWorkspace w = carve_levels(workspace, n_nodes, n_edges);
+    const size_t clear_bytes = (size_t)((char *)w.out_dst - (char *)w.ctl);
+    ASNN_HIP_TRY(hipMemsetAsync(w.ctl, 0, clear_bytes, s));
+    ASNN_HIP_TRY(hipMemsetAsync(required_out, 0, sizeof(int32_t) * (size_t)n_nodes, s));
+    if (n_edges > 0) {
+        // transposed: count and group the connections by destination
+        hipLaunchKernelGGL(degree_kernel, dim3(blocks_for((size_t)n_edges, kThreads, 65535)), dim3(kThreads), 0, s, dst,
+                           src, n_edges, n_nodes, w.indeg, w.out_ptr, w.ctl);
+        ASNN_HIP_TRY(hipGetLastError());
+    }
+    ASNN_TRY(exclusive_scan_i32(w.out_ptr, w.out_ptr, (size_t)n_nodes + 1, w.scan_tmp, s));
+    if (n_edges > 0) {
+        hipLaunchKernelGGL(fill_out_kernel, dim3(blocks_for((size_t)n_edges, kThreads, 65535)), dim3(kThreads), 0, s,
+                           dst, src, n_edges, n_nodes, (const int32_t *)w.out_ptr, w.cursor, w.out_dst);
+        ASNN_HIP_TRY(hipGetLastError());
+    }
+    if (n_outputs > 0) {
+        hipLaunchKernelGGL(seed_outputs_kernel, dim3(blocks_for((size_t)n_outputs, kThreads)), dim3(kThreads), 0, s,
+                           output_ids, n_outputs, n_nodes, required_out, w.frontier_a, w.ctl);
+        ASNN_HIP_TRY(hipGetLastError());
+    }
+    int host_ctl[kCtlInts];
+    int k = 0;
+    for (;;) {
+        for (int i = 0; i < kSweepsPerSync; ++i, ++k) {
+            const int32_t *fin = (k & 1) ? w.frontier_b : w.frontier_a;
+            int32_t *fout = (k & 1) ? w.frontier_a : w.frontier_b;
+            hipLaunchKernelGGL(reach_sweep_kernel, dim3(kSweepBlocks), dim3(kThreads), 0, s, k,
+                               (const int32_t *)w.out_ptr, (const int32_t *)w.out_dst, required_out, fin, fout, w.ctl);
+            ASNN_HIP_TRY(hipGetLastError());
+        }
+        ASNN_HIP_TRY(hipMemcpyAsync(host_ctl, w.ctl, sizeof(host_ctl), hipMemcpyDeviceToHost, s));
+        ASNN_HIP_TRY(hipStreamSynchronize(s));
+        if (host_ctl[kErr] != 0) return host_ctl[kErr];
+        if (host_ctl[kCount0 + k % 3] == 0) break;
+        if (k > n_nodes) break;          // every sweep with a non-empty frontier marks new nodes: at most n_nodes sweeps
+    }
+    *n_required_out = host_ctl[kAssigned];
+    return ASNN_OK;
+}
+
+extern "C" size_t asnn_filter_workspace_bytes(int64_t n_edges) {
+    if (n_edges < 0) return 0;
+    return carve_filter(nullptr, n_edges).bytes;
+}
+
+extern "C" int asnn_filter_required(int32_t n_nodes, int64_t n_edges, const int32_t *src, const int32_t *dst,
+                                    const float *w, const int32_t *required, int32_t *src_out, int32_t *dst_out,
+                                    float *w_out, int64_t *n_kept_out, void *workspace, size_t workspace_bytes,
+                                    void *stream) {
+    if (n_nodes <= 0 || n_edges < 0 || n_edges >= (int64_t)INT32_MAX) return ASNN_ERR_SIZE;
+    if (!required || !n_kept_out || !workspace) return ASNN_ERR_NULL;
+    if (n_edges > 0 && (!src || !dst || !w || !src_out || !dst_out || !w_out)) return ASNN_ERR_NULL;
+    if (((uintptr_t)workspace & 255u) != 0 || workspace_bytes < asnn_filter_workspace_bytes(n_edges))
+        return ASNN_ERR_WORKSPACE;
+    if (n_edges == 0) { *n_kept_out = 0; return ASNN_OK; }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    FilterWorkspace ws = carve_filter(workspace, n_edges);
+    ASNN_HIP_TRY(hipMemsetAsync(ws.err, 0, 256, s));
+    const unsigned eb = blocks_for((size_t)n_edges + 1, kThreads, 65535);
+    hipLaunchKernelGGL(keep_flag_kernel, dim3(eb), dim3(kThreads), 0, s, src, dst, required, n_edges, n_nodes, ws.pos,
+                       ws.err);
+    ASNN_HIP_TRY(hipGetLastError());
+    ASNN_TRY(exclusive_scan_i32(ws.pos, ws.pos, (size_t)n_edges + 1, ws.scan_tmp, s));
+    hipLaunchKernelGGL(compact_edges_kernel, dim3(eb), dim3(kThreads), 0, s, src, dst, w, (const int32_t *)ws.pos,
+                       n_edges, src_out, dst_out, w_out);
+    ASNN_HIP_TRY(hipGetLastError());
+    int host_err = 0;
+    int32_t kept = 0;
+    ASNN_HIP_TRY(hipMemcpyAsync(&host_err, ws.err, sizeof(int), hipMemcpyDeviceToHost, s));
+    ASNN_HIP_TRY(hipMemcpyAsync(&kept, ws.pos + n_edges, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    ASNN_HIP_TRY(hipStreamSynchronize(s));
+    *n_kept_out = kept;
+    return host_err;
+}

@@ -55,3 +55,18 @@ def brute_levels(n_nodes, edges):
         return best
 
     return [longest(v) for v in range(n_nodes)]
+
+
+def brute_required(n_nodes, edges, output_ids):
+    """v is required iff some path leads from v to an output (outputs included), by forward search from each v."""
+    outgoing = {v: [] for v in range(n_nodes)}
+    for e in edges:
+        outgoing[int(e[0])].append(int(e[1]))
+    outs = set(int(o) for o in output_ids)
+
+    def reaches(v):
+        if v in outs:
+            return True
+        return any(reaches(b) for b in outgoing[v])
+
+    return [reaches(v) for v in range(n_nodes)]

@@ -392,3 +392,37 @@ def test_schedule_choice_is_reported(amd):
     assert amd.asnn_activate_schedule(g, 1 << 20, True, 0) == "levels"      # big levels
     with pytest.raises(amd.AsnnError):
         amd.asnn_activate_schedule(g, wl.B, False, DATAFLOW)
+
+
+@pytest.mark.parametrize("idx,scale", [(1, "small"), (3, "small"), (4, "small"), (5, "small"), (3, "full")])
+def test_required_set_and_filtered_activation(amd, idx, scale):
+    """The set R of the segmentation algorithm on the GPU: bit-exact mask, the
+    kept connections are exactly those that end in R in their original order,
+    and activating the kept connections gives the same bits on every node of R."""
+    wl = make_config(idx, scale)
+    dev = "cuda:0"
+    src = torch.from_numpy(wl.src).to(dev); dst = torch.from_numpy(wl.dst).to(dev); w = torch.from_numpy(wl.w).to(dev)
+    outs = torch.from_numpy(wl.output_ids).to(dev)
+    req, n_req = amd.asnn_required_set(wl.n_nodes, src, dst, outs)
+    want = oracle.required(wl.n_nodes, wl.src, wl.dst, wl.output_ids)
+    assert (req.cpu().numpy().astype(bool) == want).all() and n_req == int(want.sum())
+    ks, kd, kw = amd.asnn_filter_required(wl.n_nodes, src, dst, w, req)
+    keep = want[wl.dst]
+    assert (ks.cpu().numpy() == wl.src[keep]).all() and (kd.cpu().numpy() == wl.dst[keep]).all()
+    assert (kw.cpu().numpy() == wl.w[keep]).all()
+    full = amd.Network(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.output_ids)
+    cut = amd.Network(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.output_ids, required_only=True)
+    assert cut.n_required == int(want.sum()) and cut.src.numel() == int(keep.sum())
+    Vf, Yf = full.activate(wl.X); full.check(wl.B)
+    Vc, Yc = cut.activate(wl.X); cut.check(wl.B)
+    assert torch.equal(Yf, Yc)
+    vf = full.values_original_order(Vf).cpu().numpy(); vc = cut.values_original_order(Vc).cpu().numpy()
+    assert (vf[want] == vc[want]).all()
+    # an output id listed twice, or none at all
+    req2, n2 = amd.asnn_required_set(wl.n_nodes, src, dst, torch.cat([outs, outs[:1]]))
+    assert n2 == n_req and torch.equal(req2, req)
+    req0, n0 = amd.asnn_required_set(wl.n_nodes, src, dst, outs[:0])
+    assert n0 == 0 and int(req0.sum()) == 0
+    with pytest.raises(amd.AsnnError) as e:
+        amd.asnn_required_set(wl.n_nodes, src, dst, torch.tensor([wl.n_nodes], dtype=torch.int32, device=dev))
+    assert e.value.code == -3

@@ -9,7 +9,7 @@ import numpy as np
 import pytest
 
 import oracle
-from brute_force import brute_levels, brute_values
+from brute_force import brute_levels, brute_required, brute_values
 from workloads import make_config, layered_skip, tiny_neat
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
@@ -344,3 +344,45 @@ def test_error_paths():
     assert e.value.code == -4
     lv, nl = oracle.levels(0, [], [])
     assert nl == 0 and lv.shape[0] == 0
+
+
+# ---------------------------------------------------------------- required set
+def test_required_set_by_brute_force_and_in_the_segmentation():
+    """R = nodes from which an output is reachable.  Pinned by forward search
+    from every node on small DAGs, and through the paper's segmentation: with
+    R given, its layers hold exactly the required nodes, level by level."""
+    rng = np.random.default_rng(21)
+    for trial in range(30):
+        n = int(rng.integers(5, 13))
+        order = rng.permutation(n)
+        m = int(rng.integers(n // 2, 2 * n))
+        edges = []
+        for _ in range(m):
+            i, j = sorted(rng.choice(n, size=2, replace=False))
+            edges.append((int(order[i]), int(order[j])))
+        outs = rng.choice(n, size=int(rng.integers(1, 3)), replace=False)
+        src = [e[0] for e in edges]; dst = [e[1] for e in edges]
+        got = oracle.required(n, src, dst, outs)
+        assert got.tolist() == brute_required(n, edges, outs)
+        # the kept connections are those that end in R; levels of the kept graph, restricted to R,
+        # are the layers the segmentation produces when it is handed R
+        keep = got[np.array(dst)] if edges else np.zeros(0, bool)
+        ksrc = np.array(src, np.int32)[keep]; kdst = np.array(dst, np.int32)[keep]
+        lv, _ = oracle.levels(n, ksrc, kdst)
+        indeg = np.bincount(kdst, minlength=n)
+        IN = [v for v in range(n) if indeg[v] == 0]          # every root acts as an input layer here
+        L = oracle.segment_network(set(np.nonzero(got)[0].tolist()), IN, outs.tolist(), set(zip(ksrc.tolist(), kdst.tolist())))
+        for k, layer in enumerate(L):
+            assert layer == {v for v in range(n) if got[v] and lv[v] == k + 1}
+        assigned = set().union(*L) if L else set()
+        assert assigned == {v for v in range(n) if got[v] and lv[v] > 0}
+
+
+def test_required_set_preserves_outputs():
+    wl = make_config(1, "small")
+    req = oracle.required(wl.n_nodes, wl.src, wl.dst, wl.output_ids)
+    assert req[wl.output_ids].all() and not req.all()          # config 1 has dead-end hidden nodes
+    keep = req[wl.dst]
+    full = oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.X)
+    cut = oracle.activate(wl.n_nodes, wl.src[keep], wl.dst[keep], wl.w[keep], wl.input_ids, wl.X)
+    assert (full[req] == cut[req]).all()
