@@ -117,8 +117,8 @@ def main():
         paper_regime()
         return
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; samples and networks shard without any exchange "
-              "(see DESIGN.md), but no multi-GPU figure is produced here. Use --gpus 1.", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU (batch columns and networks of a population would shard "
+              "without any exchange step, but no multi-GPU figure is produced here). Use --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

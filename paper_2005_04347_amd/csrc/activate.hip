@@ -552,13 +552,30 @@ int launch_level_vec(const LevelArgs &a, int hb, int mb, int lb, int le) {
     return launch_level<VEC, 1, ACC>(a, hb, mb, lb, le);
 }
 
-template <typename ACC>
-int launch_level_any(const LevelArgs &a, int hb, int mb, int lb, int le) {
-    if (a.B % 4 == 0) return launch_level_vec<4, ACC>(a, hb, mb, lb, le);
-    if (a.B % 2 == 0) return launch_level_vec<2, ACC>(a, hb, mb, lb, le);
-    return launch_level_vec<1, ACC>(a, hb, mb, lb, le);
+// Lane layout for a batch width.  A full wavefront per tile (64 lanes, wave-uniform connection:
+// scalar (col, w), one source row per load instruction) is much cheaper per byte than the grouped
+// layout, so the widest vector that still fills more than half a wavefront wins; only batches of
+// 32 columns or fewer fall back to lane groups.
+//
+// The dataflow schedule is latency-bound instead (a row is a chain of gather rounds), so there the
+// widest vector always wins: it puts the most connections into one round.
+inline int vec_for(int B, bool dataflow) {
+    if (!dataflow) {
+        if (B % 4 == 0 && B / 4 > 32) return 4;
+        if (B % 2 == 0 && B / 2 > 32) return 2;
+        if (B > 32) return 1;
+    }
+    return (B % 4 == 0) ? 4 : (B % 2 == 0 ? 2 : 1);
 }
 
+template <typename ACC>
+int launch_level_any(const LevelArgs &a, int hb, int mb, int lb, int le) {
+    switch (vec_for(a.B, false)) {
+        case 4: return launch_level_vec<4, ACC>(a, hb, mb, lb, le);
+        case 2: return launch_level_vec<2, ACC>(a, hb, mb, lb, le);
+        default: return launch_level_vec<1, ACC>(a, hb, mb, lb, le);
+    }
+}
 
 struct DataflowArgs {
     const int32_t *unit_ptr;
@@ -608,14 +625,16 @@ int launch_dataflow_vec(const LevelArgs &a, const DataflowArgs &d) {
 
 template <typename ACC>
 int launch_dataflow_any(const LevelArgs &a, const DataflowArgs &d) {
-    if (a.B % 4 == 0) return launch_dataflow_vec<4, ACC>(a, d);
-    if (a.B % 2 == 0) return launch_dataflow_vec<2, ACC>(a, d);
-    return launch_dataflow_vec<1, ACC>(a, d);
+    switch (vec_for(a.B, true)) {
+        case 4: return launch_dataflow_vec<4, ACC>(a, d);
+        case 2: return launch_dataflow_vec<2, ACC>(a, d);
+        default: return launch_dataflow_vec<1, ACC>(a, d);
+    }
 }
 
-// Batch columns per tile and tiles per row for a given B (the same choice the launchers make).
+// Tiles per row of the dataflow schedule for a given B (the same choice its launcher makes).
 inline int tiles_for(int B) {
-    const int vec = (B % 4 == 0) ? 4 : (B % 2 == 0 ? 2 : 1);
+    const int vec = vec_for(B, true);
     const int vecs = B / vec;
     int lpg = 1;
     while (lpg < 64 && lpg < vecs) lpg <<= 1;
