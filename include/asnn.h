@@ -125,7 +125,9 @@ int asnn_filter_required(int32_t n_nodes, int64_t n_edges, const int32_t *src, c
  * Level-contiguous, destination-sorted CSR (replaces the paper's per-node
  * record with its inNodes / inWeights arrays and the array sorted by layer).
  * Packed order: by level; inside a level by in-degree class (heavy, medium,
- * light); ties by original id.  The connections of one node keep their
+ * light); inside the light class the short rows (in-degree d with
+ * 4*d <= 3*floor(n_edges/n_nodes)) come last, so that a level does not end on
+ * long rows; ties by original id.  The connections of one node keep their
  * edge-list order.
  *
  * The packed network is described by an asnn_packed record.  The CALLER

@@ -11,7 +11,8 @@
 // Everything is built from two stable radix sorts (nodes by level key, edges
 // by packed destination) and prefix sums, so the packed arrays are a
 // deterministic function of the input: a node's connections keep their
-// edge-list order and ties between nodes are broken by original id.
+// edge-list order; nodes are ordered by level, in-degree class, short-row
+// flag, then original id.
 #include "asnn_common.h"
 
 namespace asnn {
@@ -36,16 +37,25 @@ __global__ void indegree_kernel(const int32_t *__restrict__ src, const int32_t *
     }
 }
 
-// key = 3*level + class (0 heavy, 1 medium, 2 light): heavier nodes lead their level.
+// Rows of a level start in packed order, so a level should end with short rows: when its
+// last rows are long ones the launch drains with most of the chip idle.  Inside the light
+// class the rows with at most 3/4 of the mean in-degree (about a fifth of the rows for
+// Poisson-like degrees, one fill of the chip) go last; everything else keeps the order of
+// the original ids, which keeps the rows of one network of a population together.
+// key = ((3*level + class) << 1) | short, class 0 heavy, 1 medium, 2 light.
+constexpr int kRankBits = 1;
+
 __global__ void node_key_kernel(const int32_t *__restrict__ level, const int32_t *__restrict__ indeg, int32_t n_nodes,
-                                int32_t n_levels, uint32_t *__restrict__ keys, uint32_t *__restrict__ vals, int *err) {
+                                int32_t n_levels, int32_t mean_indegree, uint32_t *__restrict__ keys,
+                                uint32_t *__restrict__ vals, int *err) {
     const int v = blockIdx.x * blockDim.x + threadIdx.x;
     if (v >= n_nodes) return;
     int32_t l = level[v];
     if (l < 0 || l >= n_levels) { flag_error(err, ASNN_ERR_INDEX); l = 0; }
     const int32_t d = indeg[v];
     const uint32_t cls = d >= ASNN_HEAVY_INDEGREE ? 0u : (d >= ASNN_MEDIUM_INDEGREE ? 1u : 2u);
-    keys[v] = (uint32_t)ASNN_CLASSES * (uint32_t)l + cls;
+    const uint32_t is_short = (cls == 2u && 4 * (int64_t)d <= 3 * (int64_t)mean_indegree) ? 1u : 0u;
+    keys[v] = (((uint32_t)ASNN_CLASSES * (uint32_t)l + cls) << kRankBits) | is_short;
     vals[v] = (uint32_t)v;
 }
 
@@ -62,7 +72,7 @@ __global__ void permutation_kernel(const uint32_t *__restrict__ sorted_ids, cons
     packed_deg[i] = indeg[v];
 }
 
-// level_ptr[k] = number of nodes whose key is < k  (k = 0 .. 3*n_levels).
+// level_ptr[k] = number of nodes whose (level, class) key is < k  (k = 0 .. 3*n_levels).
 __global__ void level_ptr_kernel(const uint32_t *__restrict__ sorted_keys, int32_t n_nodes, int32_t n_keys,
                                  int32_t *__restrict__ level_ptr) {
     const int k = blockIdx.x * blockDim.x + threadIdx.x;
@@ -70,7 +80,7 @@ __global__ void level_ptr_kernel(const uint32_t *__restrict__ sorted_keys, int32
     int lo = 0, hi = n_nodes;
     while (lo < hi) {
         const int mid = lo + (hi - lo) / 2;
-        if (sorted_keys[mid] < (uint32_t)k) lo = mid + 1; else hi = mid;
+        if ((sorted_keys[mid] >> kRankBits) < (uint32_t)k) lo = mid + 1; else hi = mid;
     }
     level_ptr[k] = lo;
 }
@@ -118,7 +128,7 @@ __global__ void unit_ptr_kernel(const uint32_t *__restrict__ sorted_keys, const 
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i > n_nodes) return;
     if (i == n_nodes) { unit_ptr[seg_unit_start[n_keys]] = n_nodes; return; }
-    const int k = (int)sorted_keys[i];
+    const int k = (int)(sorted_keys[i] >> kRankBits);
     const int g = unit_rows_of_class(k % ASNN_CLASSES);
     const int off = i - level_ptr[k];
     if (off % g == 0) unit_ptr[seg_unit_start[k] + off / g] = i;
@@ -170,7 +180,7 @@ extern "C" int asnn_pack_csr(const int32_t *src, const int32_t *dst, const float
             *inv_perm = packed->inv_perm, *row_ptr = packed->row_ptr, *col = packed->col, *unit_ptr = packed->unit_ptr;
     float *w_packed = packed->w;
     if (n_nodes <= 0 || n_edges < 0 || n_edges >= (int64_t)INT32_MAX || n_levels <= 0 ||
-        n_levels > n_nodes || n_levels >= (1 << 29))
+        n_levels > n_nodes || n_levels >= (1 << 28))
         return ASNN_ERR_SIZE;
     if (!level || !level_ptr || !level_ptr_host || !perm || !inv_perm || !row_ptr || !unit_ptr || !workspace)
         return ASNN_ERR_NULL;
@@ -190,10 +200,10 @@ extern "C" int asnn_pack_csr(const int32_t *src, const int32_t *dst, const float
     }
     // nodes: stable sort by (level, in-degree class) key
     hipLaunchKernelGGL(node_key_kernel, dim3(blocks_for(n, kThreads)), dim3(kThreads), 0, s, level,
-                       (const int32_t *)ws.indeg, n_nodes, n_levels, ws.keys_a, ws.vals_a, ws.err);
+                       (const int32_t *)ws.indeg, n_nodes, n_levels, (int32_t)(n_edges / n_nodes), ws.keys_a, ws.vals_a, ws.err);
     ASNN_HIP_TRY(hipGetLastError());
     uint32_t *ks, *vs;
-    ASNN_TRY(radix_sort_pairs_u32(ws.keys_a, ws.vals_a, ws.keys_b, ws.vals_b, n, bits_for((uint64_t)n_keys), ws.tmp, s,
+    ASNN_TRY(radix_sort_pairs_u32(ws.keys_a, ws.vals_a, ws.keys_b, ws.vals_b, n, bits_for((uint64_t)n_keys << kRankBits), ws.tmp, s,
                                   &ks, &vs));
     hipLaunchKernelGGL(permutation_kernel, dim3(blocks_for(n + 1, kThreads)), dim3(kThreads), 0, s,
                        (const uint32_t *)vs, (const int32_t *)ws.indeg, n_nodes, perm, inv_perm, ws.packed_deg);

@@ -36,7 +36,9 @@ def expected_pack(wl, level, n_levels, heavy=256, medium=32):
     n = wl.n_nodes
     indeg = np.bincount(wl.dst, minlength=n)
     key = 3 * level.astype(np.int64) + np.where(indeg >= heavy, 0, np.where(indeg >= medium, 1, 2))
-    perm = np.argsort(key, kind="stable").astype(np.int32)
+    mean = wl.src.shape[0] // n
+    full_key = key * 2 + ((indeg < medium) & (4 * indeg <= 3 * mean))     # short light rows end their level
+    perm = np.argsort(full_key, kind="stable").astype(np.int32)
     inv = np.empty(n, dtype=np.int32)
     inv[perm] = np.arange(n, dtype=np.int32)
     level_ptr = np.searchsorted(key[perm], np.arange(3 * n_levels + 1), side="left").astype(np.int32)
