@@ -46,7 +46,7 @@ def measured_traffic(config, flags):
     return None
 
 
-def paper_regime():
+def paper_regime(flags=0):
     """The paper's own experiment on this machine: ONE input vector per activation, time against the
     number of connections for shallow and deep networks, GPU (10 runs averaged, as in the paper's
     experimental setup) against the sequential oracle (5 runs averaged).  Prints one JSON line per network."""
@@ -69,20 +69,20 @@ def paper_regime():
             V = torch.empty((wl.n_nodes, 1), device="cuda")
             Y = torch.empty((len(wl.output_ids), 1), device="cuda")
             for _ in range(5):
-                net.activate(X, V=V, Y=Y)
+                net.activate(X, V=V, Y=Y, flags=flags)
             torch.cuda.synchronize()
             # resident: events around 10 activations; with transfers: host X in, host Y out, as the paper timed it
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
             for _ in range(10):
-                net.activate(X, V=V, Y=Y)
+                net.activate(X, V=V, Y=Y, flags=flags)
             e1.record()
             torch.cuda.synchronize()
             gpu_us = e0.elapsed_time(e1) * 1e3 / 10
             t0 = time.perf_counter()
             for _ in range(10):
                 Xd = torch.from_numpy(wl.X).cuda()
-                net.activate(Xd, V=V, Y=Y)
+                net.activate(Xd, V=V, Y=Y, flags=flags)
                 y_host = Y.cpu()
             copy_us = (time.perf_counter() - t0) * 1e6 / 10
             oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.X)
@@ -93,7 +93,9 @@ def paper_regime():
                 cpu_us += tm["activation_seconds"] * 1e6 / 5
             err = float(np.abs(net.values_original_order(V).cpu().numpy().astype(np.float64) - ref).max())
             print(json.dumps({"regime": "paper: batch 1", "connections": wl.n_edges, "nodes": wl.n_nodes,
-                              "levels": net.n_levels, "gpu_us_resident": round(gpu_us, 1),
+                              "levels": net.n_levels,
+                              "schedule_taken": amd.asnn_activate_schedule(net.graph, 1, True, flags),
+                              "gpu_us_resident": round(gpu_us, 1),
                               "gpu_us_with_host_copies": round(copy_us, 1), "cpu_oracle_us": round(cpu_us, 1),
                               "speedup_resident": round(cpu_us / gpu_us, 2),
                               "speedup_with_host_copies": round(cpu_us / copy_us, 2), "max_abs_err": err}), flush=True)
@@ -106,7 +108,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--flags", type=int, default=0, help="asnn_activate flags (2 = fp32 accumulate)")
-    ap.add_argument("--schedule", choices=["auto", "levels", "dataflow"], default="auto",
+    ap.add_argument("--schedule", choices=["auto", "levels", "dataflow", "workgroup"], default="auto",
                     help="level launches, persistent dataflow launch, or the library's own choice")
     ap.add_argument("--graph", action="store_true", help="capture one asnn_activate in a HIP graph and time replays")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
@@ -114,7 +116,7 @@ def main():
                     help="batch-1 latency against connections, as in the paper's figures (prints one line per network)")
     args = ap.parse_args()
     if args.paper_regime:
-        paper_regime()
+        paper_regime({"auto": 0, "levels": 4, "dataflow": 8, "workgroup": 16}[args.schedule])
         return
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (batch columns and networks of a population would shard "
@@ -140,7 +142,8 @@ def main():
     V = torch.empty((wl.n_nodes, B), dtype=torch.float32, device=dev)
     Y = torch.empty((len(wl.output_ids), B), dtype=torch.float32, device=dev)
 
-    flags = args.flags | {"auto": 0, "levels": amd.FLAG_LEVEL_LAUNCHES, "dataflow": amd.FLAG_DATAFLOW}[args.schedule]
+    flags = args.flags | {"auto": 0, "levels": amd.FLAG_LEVEL_LAUNCHES, "dataflow": amd.FLAG_DATAFLOW,
+                          "workgroup": amd.FLAG_WORKGROUP}[args.schedule]
 
     def step():
         net.activate(X, V=V, Y=Y, flags=flags)

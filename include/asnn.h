@@ -63,6 +63,7 @@ extern "C" {
                                     fp64 sigmoid, rounded once to fp32 on store) */
 #define ASNN_FLAG_LEVEL_LAUNCHES 4u  /* force one launch per level */
 #define ASNN_FLAG_DATAFLOW 8u        /* force the persistent dataflow launch (needs the workspace) */
+#define ASNN_FLAG_WORKGROUP 16u      /* force one workgroup per tile of batch columns */
 
 /* In-degree classes.  Inside a level the packed order lists the heavy nodes
  * (in-degree >= ASNN_HEAVY_INDEGREE) first, then the medium ones
@@ -166,16 +167,26 @@ int asnn_pack_csr(const int32_t *src, const int32_t *dst, const float *w, const 
 /* ---- 3. activate -------------------------------------------------------
  * Full activation of the packed network (or of a packed disjoint union of
  * networks: a population is activated by one call) for B input vectors
- * (activation kernel listing).  Two schedules compute the same bits:
+ * (activation kernel listing).  Three schedules compute the same bits:
  *   - level launches: one launch per level on the stream; the boundary
  *     between two launches is the paper's layer barrier;
  *   - dataflow: one persistent launch; workgroups claim work units in packed
  *     order and a row waits only for its own source rows (per-row ready
  *     flags), so a deep, narrow network is not paced by a barrier per layer
  *     (the paper names grid-wide synchronisation as future work).  Needs the
- *     workspace and n_nodes*B*4 < 4 GiB.
- * By default the dataflow schedule is taken when a workspace is given and the
- * average level is small; ASNN_FLAG_LEVEL_LAUNCHES / ASNN_FLAG_DATAFLOW force one.
+ *     workspace and n_nodes*B*4 < 4 GiB;
+ *   - workgroup: the shape of the paper's kernel, one workgroup walks all
+ *     levels with a workgroup barrier between two levels; batch columns are
+ *     independent, so there is one such workgroup per tile of up to 64
+ *     columns and nothing is exchanged between workgroups.  Sensor staging
+ *     and the copy to Y happen in the same launch: an activation is one
+ *     launch.  Meant for small networks and narrow batches (the paper's own
+ *     regime: one input vector, thousands of connections), where launches
+ *     and level hand-overs cost more than the connections.
+ * By default: the workgroup schedule up to n_edges*B = 32768; else the
+ * dataflow schedule when a workspace is given and the average level is small;
+ * else level launches.  ASNN_FLAG_LEVEL_LAUNCHES / ASNN_FLAG_DATAFLOW /
+ * ASNN_FLAG_WORKGROUP force one (more than one of them: SIZE).
  *   packed      host record filled by asnn_pack_csr
  *   input_ids   device int32[n_inputs]  original ids; X row k feeds input_ids[k]
  *               (the ids given to asnn_build_levels)
@@ -193,8 +204,9 @@ int asnn_pack_csr(const int32_t *src, const int32_t *dst, const float *w, const 
  * that asnn_activate_status reports. */
 size_t asnn_activate_workspace_bytes(int32_t n_nodes, int32_t B);
 /* Which schedule asnn_activate takes for this record, batch width, workspace
- * (given or not) and flags: 0 = one launch per level, 1 = dataflow, < 0 = the
- * error asnn_activate would return for this choice.  Launches nothing. */
+ * (given or not) and flags: 0 = one launch per level, 1 = dataflow, 2 = one
+ * workgroup per tile, < 0 = the error asnn_activate would return for this
+ * choice.  Launches nothing. */
 int asnn_activate_schedule(const asnn_packed *packed, int32_t B, int has_workspace, uint32_t flags);
 int asnn_activate(const asnn_packed *packed,
                   const int32_t *input_ids, int32_t n_inputs,

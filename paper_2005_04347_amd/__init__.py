@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     FLAG_DATAFLOW,
     FLAG_LEVEL_LAUNCHES,
     FLAG_RAW_INPUTS,
+    FLAG_WORKGROUP,
     HEAVY_INDEGREE,
     MEDIUM_INDEGREE,
     Network,

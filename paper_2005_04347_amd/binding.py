@@ -21,6 +21,7 @@ FLAG_RAW_INPUTS = 1
 FLAG_ACC_F32 = 2
 FLAG_LEVEL_LAUNCHES = 4
 FLAG_DATAFLOW = 8
+FLAG_WORKGROUP = 16
 HEAVY_INDEGREE = 256
 MEDIUM_INDEGREE = 32
 CLASSES = 3
@@ -264,12 +265,12 @@ def asnn_activate(g: PackedGraph, input_ids: torch.Tensor, X: torch.Tensor,
 
 
 def asnn_activate_schedule(g: PackedGraph, B: int, has_workspace: bool = True, flags: int = 0) -> str:
-    """'levels' or 'dataflow': the schedule asnn_activate would take."""
+    """'levels', 'dataflow' or 'workgroup': the schedule asnn_activate would take."""
     lib = load()
     rc = lib.asnn_activate_schedule(ctypes.byref(g.record), B, int(has_workspace), flags)
     if rc < 0:
         raise AsnnError(rc, "asnn_activate_schedule")
-    return "dataflow" if rc == 1 else "levels"
+    return ("levels", "dataflow", "workgroup")[rc]
 
 
 def asnn_activate_status(workspace: Optional[torch.Tensor]) -> None:

@@ -474,6 +474,205 @@ __global__ __launch_bounds__(kMixedBlock) void dataflow_kernel(const int32_t *__
     }
 }
 
+// ------------------------------------------------------- one workgroup per tile
+// The paper's kernel shape: one workgroup walks all levels with a workgroup
+// barrier between two levels, and nothing is exchanged between workgroups.
+// Batch columns are independent, so there is one such workgroup per tile of
+// batch columns; it also stages the sensor values of its tile first and
+// copies the output rows last, which makes the whole activation one launch.
+// A small network spends its time on launches and level hand-overs, not on
+// connections: this schedule pays about a microsecond per level.
+//
+// Lanes: LPG lanes cover the tile's columns, so a wavefront holds G = 64/LPG
+// lane groups.  Light rows are taken one per lane group, each group walking
+// its row's connections serially in edge-list order (for B = 1 that is the
+// paper's thread per node with a serial loop); medium rows one per wavefront,
+// the groups striding over the connections; heavy rows by all 16 wavefronts.
+
+// Serial weighted sum of one row's connections for a lane group (per-lane col/w loads,
+// U gathers in flight).  e_begin/e_end may differ between the groups of a wavefront.
+template <int VEC, typename ACC, int U>
+__device__ inline void row_sum_serial(const int32_t *__restrict__ col, const float *__restrict__ w, const float *V, int B,
+                                      int e_begin, int e_end, int c0, ACC (&acc)[VEC]) {
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) acc[j] = ACC(0);
+    const float *Vc = V + c0;
+    for (int e = e_begin; e < e_end; e += U) {
+        int cc[U];
+        float ww[U];
+        float vals[U][VEC];
+#pragma unroll
+        for (int k = 0; k < U; ++k) {
+            const int ek = min(e + k, e_end - 1);        // padded slots re-read the last connection
+            cc[k] = col[ek];
+            ww[k] = w[ek];
+        }
+#pragma unroll
+        for (int k = 0; k < U; ++k) load_vec<VEC>(Vc + (size_t)cc[k] * (size_t)B, vals[k]);
+#pragma unroll
+        for (int k = 0; k < U; ++k)
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) {
+                const ACC t = acc[j] + (ACC)ww[k] * (ACC)vals[k][j];
+                acc[j] = (e + k < e_end) ? t : acc[j];
+            }
+    }
+}
+
+// STAGED: the packed connections and the workgroup's tile of V live in LDS for the whole
+// activation (dynamic LDS: V tile [n_nodes][T] floats, then row_ptr, col, w, level_ptr), so a level costs
+// LDS round trips instead of L2 ones; the tile is copied to V in global memory at the end.
+template <int VEC, int LPG, typename ACC, int U, bool STAGED>
+__global__ __launch_bounds__(kMixedBlock) void workgroup_kernel(
+    const int32_t *__restrict__ level_ptr, int n_levels, const int32_t *__restrict__ row_ptr,
+    const int32_t *__restrict__ col, const float *__restrict__ w, float *V, int B,
+    const int32_t *__restrict__ input_ids, const int32_t *__restrict__ inv_perm, const float *__restrict__ X,
+    int n_inputs, int raw, const int32_t *__restrict__ output_ids, float *__restrict__ Y, int n_outputs, int n_nodes,
+    int n_edges) {
+    constexpr int T = LPG * VEC;
+    constexpr int G = kWave / LPG;
+    __shared__ ACC part[kMixedWaves][T];
+    extern __shared__ __align__(16) unsigned char staged[];
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
+    const int lane = threadIdx.x & (kWave - 1);
+    const int g = lane / LPG;                          // lane group inside the wavefront
+    const int slot = wave * G + g;                     // lane group inside the workgroup
+    constexpr int kSlots = kMixedWaves * G;
+    const int ct = (lane % LPG) * VEC;                 // first column of this lane inside the tile
+    const int c = blockIdx.x * T + ct;
+    const bool col_ok = c < B;
+
+    // where the sums read: the LDS copies, or global memory
+    float *s_V = reinterpret_cast<float *>(staged);
+    int32_t *s_row_ptr = reinterpret_cast<int32_t *>(staged + (((size_t)n_nodes * T * 4 + 15) & ~(size_t)15));
+    int32_t *s_col = s_row_ptr + (n_nodes + 1);
+    float *s_w = reinterpret_cast<float *>(s_col + n_edges);
+    int32_t *s_level_ptr = reinterpret_cast<int32_t *>(s_w + n_edges);
+    const int32_t *lp = STAGED ? s_level_ptr : level_ptr;
+    const int32_t *rp = STAGED ? s_row_ptr : row_ptr;
+    const int32_t *cl = STAGED ? s_col : col;
+    const float *wt = STAGED ? s_w : w;
+    const float *Vr = STAGED ? s_V : V;
+    const int ld = STAGED ? T : B;                     // row stride of Vr
+    const int cr = STAGED ? ct : (col_ok ? c : 0);     // this lane's first column in Vr
+    if constexpr (STAGED) {
+        for (int i = threadIdx.x; i <= n_nodes; i += kMixedBlock) s_row_ptr[i] = row_ptr[i];
+        for (int i = threadIdx.x; i < n_edges; i += kMixedBlock) { s_col[i] = col[i]; s_w[i] = w[i]; }
+        for (int i = threadIdx.x; i <= ASNN_CLASSES * n_levels; i += kMixedBlock) s_level_ptr[i] = level_ptr[i];
+        __syncthreads();
+    }
+    // A staged workgroup keeps its values in LDS and copies the tile to V once at the end: a
+    // global store before a barrier would make every level wait for its acknowledgement.
+    auto put = [&](int row, const float (&out)[VEC]) {
+        if constexpr (STAGED) {
+            store_vec<VEC>(s_V + row * T + ct, out);
+        } else {
+            if (col_ok) store_vec<VEC>(V + (size_t)row * (size_t)B + c, out);
+        }
+    };
+
+    // Level 0 has no connections: sigmoid(0), then the sensors take their inputs.
+    const int level0_end = lp[ASNN_CLASSES];
+    {
+        float half[VEC];
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) half[j] = squash(ACC(0));
+        for (int r = slot; r < level0_end; r += kSlots) put(r, half);
+    }
+    __syncthreads();
+    for (int k = slot; k < n_inputs; k += kSlots) {
+        const int32_t id = input_ids[k];
+        if (id < 0 || id >= n_nodes) continue;
+        float out[VEC];
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) {
+            const float x = col_ok ? X[(size_t)k * (size_t)B + c + j] : 0.0f;
+            out[j] = raw ? x : squash((ACC)x);
+        }
+        put(inv_perm[id], out);
+    }
+    __syncthreads();
+
+    for (int l = 1; l < n_levels; ++l) {
+        const int hb = lp[ASNN_CLASSES * l], mb = lp[ASNN_CLASSES * l + 1], lb = lp[ASNN_CLASSES * l + 2],
+                  le = lp[ASNN_CLASSES * l + 3];
+        // heavy rows: all wavefronts on one row, partial sums meet in LDS in wave order
+        for (int row = hb; row < mb; ++row) {
+            const int e0 = rp[row], e1 = rp[row + 1];
+            const int chunk = (e1 - e0 + kMixedWaves - 1) / kMixedWaves;
+            const int b0 = min(e0 + wave * chunk, e1), b1 = min(b0 + chunk, e1);
+            ACC acc[VEC];
+            row_sum<VEC, LPG, ACC, U>(cl, wt, Vr, ld, b0, b1, cr, acc);
+            if (lane < LPG) {
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) part[wave][lane * VEC + j] = acc[j];
+            }
+            __syncthreads();
+            if (wave == 0 && lane < LPG) {
+                float out[VEC];
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) {
+                    ACC s = ACC(0);
+                    for (int k = 0; k < kMixedWaves; ++k) s += part[k][lane * VEC + j];
+                    out[j] = squash(s);
+                }
+                put(row, out);
+            }
+            __syncthreads();
+        }
+        // medium rows: one wavefront per row
+        for (int row = mb + wave; row < lb; row += kMixedWaves) {
+            ACC acc[VEC];
+            row_sum<VEC, LPG, ACC, U>(cl, wt, Vr, ld, rp[row], rp[row + 1], cr, acc);
+            if (lane < LPG) {
+                float out[VEC];
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) out[j] = squash(acc[j]);
+                put(row, out);
+            }
+        }
+        // light rows: one lane group per row (a full wavefront per row when the tile needs all lanes)
+        if constexpr (G == 1) {
+            for (int row = lb + wave; row < le; row += kMixedWaves) {
+                ACC acc[VEC];
+                row_sum<VEC, LPG, ACC, U>(cl, wt, Vr, ld, rp[row], rp[row + 1], cr, acc);
+                float out[VEC];
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) out[j] = squash(acc[j]);
+                put(row, out);
+            }
+        } else {
+            for (int row = lb + slot; row < le; row += kSlots) {
+                ACC acc[VEC];
+                row_sum_serial<VEC, ACC, U>(cl, wt, Vr, ld, rp[row], rp[row + 1], cr, acc);
+                float out[VEC];
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) out[j] = squash(acc[j]);
+                put(row, out);
+            }
+        }
+        __syncthreads();        // the layer barrier of the paper's kernel
+    }
+
+    if (Y != nullptr && col_ok) {
+        for (int o = slot; o < n_outputs; o += kSlots) {
+            const int32_t id = output_ids[o];
+            const bool ok = id >= 0 && id < n_nodes;
+            const size_t row = ok ? (size_t)inv_perm[id] : 0;
+#pragma unroll
+            for (int j = 0; j < VEC; ++j)
+                Y[(size_t)o * (size_t)B + c + j] = ok ? Vr[row * (size_t)ld + cr + j] : __builtin_nanf("");
+        }
+    }
+    if constexpr (STAGED) {
+        const int total = n_nodes * T;
+        for (int i = threadIdx.x; i < total; i += kMixedBlock) {
+            const int row = i / T, cc = blockIdx.x * T + i % T;
+            if (cc < B) V[(size_t)row * (size_t)B + cc] = s_V[i];
+        }
+    }
+}
+
 // Sensors: V[row of input_ids[k]][b] = sigmoid(X[k][b]) (or X raw).
 template <typename ACC>
 __global__ void stage_inputs_kernel(const int32_t *__restrict__ input_ids, const int32_t *__restrict__ inv_perm,
@@ -633,6 +832,92 @@ int launch_dataflow_any(const LevelArgs &a, const DataflowArgs &d) {
     }
 }
 
+struct WorkgroupArgs {
+    const int32_t *level_ptr;
+    int n_levels;
+    const int32_t *input_ids, *inv_perm;
+    const float *X;
+    int n_inputs, raw;
+    const int32_t *output_ids;
+    float *Y;
+    int n_outputs, n_nodes;
+    int64_t n_edges;
+};
+
+// Lane layout of the workgroup schedule.  Up to 64 columns: the widest vector, which leaves the
+// most lane groups (rows in flight) per wavefront.  Wider batches: one float per lane, 64 columns
+// per workgroup, because the workgroups are independent and more of them finish sooner.
+inline int vec_for_workgroup(int B) {
+    if (B > 64) return 1;
+    return (B % 4 == 0) ? 4 : (B % 2 == 0 ? 2 : 1);
+}
+
+inline long long tiles_for_workgroup(int B) {
+    const int vec = vec_for_workgroup(B);
+    const int vecs = B / vec;
+    int lpg = 1;
+    while (lpg < 64 && lpg < vecs) lpg <<= 1;
+    return (vecs + lpg - 1) / lpg;
+}
+
+// Dynamic LDS a staged workgroup needs; the packed network is staged when this fits the budget.
+// The static arrays of the kernel take up to 32 KB beside it.
+constexpr size_t kStagedLdsBudget = 96 * 1024;          // needs the kernel attribute raised
+constexpr size_t kStagedLdsBudgetDefault = 32 * 1024;   // fits without
+inline size_t staged_lds_bytes(int n_nodes, int64_t n_edges, int n_levels, int T) {
+    return (((size_t)n_nodes * (size_t)T * 4 + 15) & ~(size_t)15) + 4 * ((size_t)n_nodes + 1) + 8 * (size_t)n_edges +
+           4 * ((size_t)ASNN_CLASSES * (size_t)n_levels + 1);
+}
+
+template <int VEC, int LPG, typename ACC>
+int launch_workgroup(const LevelArgs &a, const WorkgroupArgs &g) {
+    const int vecs = a.B / VEC;
+    const int tiles = (vecs + LPG - 1) / LPG;
+    const size_t lds = staged_lds_bytes(g.n_nodes, g.n_edges, g.n_levels, LPG * VEC);
+    static size_t budget = 0;       // dynamic LDS this instantiation may take
+    if (budget == 0) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&workgroup_kernel<VEC, LPG, ACC, kUnroll, true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStagedLdsBudget) == hipSuccess) {
+            budget = kStagedLdsBudget;
+        } else {
+            (void)hipGetLastError();
+            budget = kStagedLdsBudgetDefault;
+        }
+    }
+    if (lds <= budget) {
+        hipLaunchKernelGGL((workgroup_kernel<VEC, LPG, ACC, kUnroll, true>), dim3((unsigned)tiles), dim3(kMixedBlock), lds,
+                           a.s, g.level_ptr, g.n_levels, a.row_ptr, a.col, a.w, a.V, a.B, g.input_ids, g.inv_perm, g.X,
+                           g.n_inputs, g.raw, g.output_ids, g.Y, g.n_outputs, g.n_nodes, (int)g.n_edges);
+    } else {
+        hipLaunchKernelGGL((workgroup_kernel<VEC, LPG, ACC, kUnroll, false>), dim3((unsigned)tiles), dim3(kMixedBlock), 0,
+                           a.s, g.level_ptr, g.n_levels, a.row_ptr, a.col, a.w, a.V, a.B, g.input_ids, g.inv_perm, g.X,
+                           g.n_inputs, g.raw, g.output_ids, g.Y, g.n_outputs, g.n_nodes, (int)g.n_edges);
+    }
+    ASNN_HIP_TRY(hipGetLastError());
+    return ASNN_OK;
+}
+
+template <int VEC, typename ACC>
+int launch_workgroup_vec(const LevelArgs &a, const WorkgroupArgs &g) {
+    const int vecs = a.B / VEC;
+    if (vecs > 32) return launch_workgroup<VEC, 64, ACC>(a, g);
+    if (vecs > 16) return launch_workgroup<VEC, 32, ACC>(a, g);
+    if (vecs > 8) return launch_workgroup<VEC, 16, ACC>(a, g);
+    if (vecs > 4) return launch_workgroup<VEC, 8, ACC>(a, g);
+    if (vecs > 2) return launch_workgroup<VEC, 4, ACC>(a, g);
+    if (vecs > 1) return launch_workgroup<VEC, 2, ACC>(a, g);
+    return launch_workgroup<VEC, 1, ACC>(a, g);
+}
+
+template <typename ACC>
+int launch_workgroup_any(const LevelArgs &a, const WorkgroupArgs &g) {
+    switch (vec_for_workgroup(a.B)) {
+        case 4: return launch_workgroup_vec<4, ACC>(a, g);
+        case 2: return launch_workgroup_vec<2, ACC>(a, g);
+        default: return launch_workgroup_vec<1, ACC>(a, g);
+    }
+}
+
 // Tiles per row of the dataflow schedule for a given B (the same choice its launcher makes).
 inline int tiles_for(int B) {
     const int vec = vec_for(B, true);
@@ -657,13 +942,20 @@ inline ActivateWorkspace carve_activate(void *ws, int32_t n_nodes, int32_t B) {
     return w;
 }
 
-// Which schedule an activation takes: 0 = one launch per level, 1 = dataflow, < 0 = error.
+// Which schedule an activation takes: 0 = one launch per level, 1 = dataflow, 2 = one workgroup
+// per tile, < 0 = error.
 int choose_schedule(const asnn_packed *packed, int32_t B, bool has_workspace, uint32_t flags);
 
 // Average connections*samples per level below which the persistent dataflow
 // launch beats one launch per level (measured on MI355X: a level launch costs
 // about 8 us however little it does).
 constexpr double kDataflowMaxLevelWork = 8.0e6;
+// Connections*samples up to which one workgroup per tile beats the schedules that spread a
+// level over the chip: it pays under a microsecond per level and a single launch, but a
+// workgroup has few rows in flight, so beyond a narrow batch of a small network the
+// other schedules win (measured on MI355X: 16k connections at B = 1 take 24 us against
+// 30 us, at B = 8 41 us against 32 us).
+constexpr int64_t kWorkgroupMaxWork = 32768;
 
 }  // namespace
 }  // namespace asnn
@@ -674,18 +966,23 @@ namespace asnn {
 namespace {
 int choose_schedule(const asnn_packed *packed, int32_t B, bool has_workspace, uint32_t flags) {
     const int32_t n_nodes = packed->n_nodes, n_levels = packed->n_levels;
-    if ((flags & ASNN_FLAG_LEVEL_LAUNCHES) && (flags & ASNN_FLAG_DATAFLOW)) return ASNN_ERR_SIZE;
+    const uint32_t forced = flags & (ASNN_FLAG_LEVEL_LAUNCHES | ASNN_FLAG_DATAFLOW | ASNN_FLAG_WORKGROUP);
+    if (forced & (forced - 1)) return ASNN_ERR_SIZE;            // more than one schedule forced
     const long long n_work = (long long)(packed->n_units - packed->first_unit) * tiles_for(B);
     const bool possible = has_workspace && packed->unit_ptr && n_levels > 1 && packed->n_units > 0 &&
                           packed->first_unit >= 0 && packed->first_unit <= packed->n_units &&
                           packed->n_units <= n_nodes && n_work > 0 && n_work < 0x7fffffffLL &&
                           (uint64_t)n_nodes * (uint64_t)B * 4u <= 0xffffffffull;
+    const bool workgroup_possible = packed->level_ptr != nullptr && tiles_for_workgroup(B) <= 0x7fffffffLL;
+    if (flags & ASNN_FLAG_WORKGROUP) return workgroup_possible ? 2 : ASNN_ERR_NULL;
     if (flags & ASNN_FLAG_DATAFLOW) {
         if (!has_workspace) return ASNN_ERR_NULL;
         if (!possible && n_levels > 1) return ASNN_ERR_SIZE;
         return possible ? 1 : 0;
     }
-    if ((flags & ASNN_FLAG_LEVEL_LAUNCHES) || !possible) return 0;
+    if (flags & ASNN_FLAG_LEVEL_LAUNCHES) return 0;
+    if (workgroup_possible && packed->n_edges * (int64_t)B <= kWorkgroupMaxWork) return 2;
+    if (!possible) return 0;
     return (double)packed->n_edges * (double)B / (double)(n_levels - 1) < kDataflowMaxLevelWork ? 1 : 0;
 }
 }  // namespace
@@ -744,6 +1041,12 @@ extern "C" int asnn_activate(const asnn_packed *packed, const int32_t *input_ids
     const bool f32 = (flags & ASNN_FLAG_ACC_F32) != 0;
     const int raw = (flags & ASNN_FLAG_RAW_INPUTS) ? 1 : 0;
     LevelArgs a{packed->row_ptr, packed->col, packed->w, V, B, s};
+
+    if (plan == 2) {        // staging, every level and the output copy in one launch
+        WorkgroupArgs g{packed->level_ptr, n_levels, input_ids, packed->inv_perm, X, n_inputs, raw,
+                        output_ids, n_outputs > 0 ? Y : nullptr, n_outputs, n_nodes, n_edges};
+        return f32 ? launch_workgroup_any<float>(a, g) : launch_workgroup_any<double>(a, g);
+    }
 
     // Level 0 has no incoming connections.  Rows that are no sensors get sigmoid(0); when every
     // row of the level is a sensor the fill is skipped.

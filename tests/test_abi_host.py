@@ -55,6 +55,9 @@ def test_header_constants_match_binding():
     assert int(re.search(r"#define ASNN_CLASSES (\d+)", text).group(1)) == b.CLASSES
     assert int(re.search(r"#define ASNN_FLAG_RAW_INPUTS (\d+)u", text).group(1)) == b.FLAG_RAW_INPUTS
     assert int(re.search(r"#define ASNN_FLAG_ACC_F32 (\d+)u", text).group(1)) == b.FLAG_ACC_F32
+    assert int(re.search(r"#define ASNN_FLAG_LEVEL_LAUNCHES (\d+)u", text).group(1)) == b.FLAG_LEVEL_LAUNCHES
+    assert int(re.search(r"#define ASNN_FLAG_DATAFLOW (\d+)u", text).group(1)) == b.FLAG_DATAFLOW
+    assert int(re.search(r"#define ASNN_FLAG_WORKGROUP (\d+)u", text).group(1)) == b.FLAG_WORKGROUP
 
 
 def test_workspace_sizes_grow_and_align(lib):
@@ -114,6 +117,8 @@ def test_argument_checks_need_no_device(lib):
     assert act(rec(lph=None)) == -1
     assert act(rec(), flags=4 | 8) == -2                      # both schedules forced
     assert act(rec(), flags=8) == -1                          # dataflow forced without a workspace
+    assert act(rec(), flags=4 | 16) == -2 and act(rec(), flags=8 | 16) == -2
+    assert act(rec(null=("level_ptr",)), flags=16) == -1      # the workgroup schedule reads the device level table
     assert lib.asnn_activate_workspace_bytes(0, 4) == 0
     nbytes = lib.asnn_activate_workspace_bytes(1000, 64)
     assert 0 < nbytes <= 4096 and nbytes % 256 == 0

@@ -49,8 +49,8 @@ def expected_pack(wl, level, n_levels, heavy=256, medium=32):
     return perm, inv, level_ptr, row_ptr, col, w
 
 
-LEVELS, DATAFLOW = 4, 8          # ASNN_FLAG_LEVEL_LAUNCHES, ASNN_FLAG_DATAFLOW
-SCHEDULES = [LEVELS, DATAFLOW]
+LEVELS, DATAFLOW, WORKGROUP = 4, 8, 16      # ASNN_FLAG_LEVEL_LAUNCHES, ASNN_FLAG_DATAFLOW, ASNN_FLAG_WORKGROUP
+SCHEDULES = [LEVELS, DATAFLOW, WORKGROUP]
 
 
 def run_gpu(amd, wl, flags=0, poison=True, X=None, net=None):
@@ -186,7 +186,7 @@ def test_heavy_rows_and_non_sensor_root(amd, B):
 def test_deterministic_and_raw_inputs(amd):
     wl = make_config(3, "small")
     net, V1, Y1 = run_gpu(amd, wl, flags=LEVELS)
-    for sched in (LEVELS, DATAFLOW, 0, DATAFLOW):
+    for sched in (LEVELS, DATAFLOW, 0, WORKGROUP, DATAFLOW, WORKGROUP):
         V2, Y2 = net.activate(wl.X, flags=sched)
         net.check(wl.B)
         assert torch.equal(V1, V2) and torch.equal(Y1, Y2)
@@ -196,6 +196,17 @@ def test_deterministic_and_raw_inputs(amd):
     assert torch.equal(V1, V2)
     with pytest.raises(amd.AsnnError):
         net.activate(wl.X, flags=DATAFLOW, use_workspace=False)
+    with pytest.raises(amd.AsnnError):
+        net.activate(wl.X, flags=DATAFLOW | WORKGROUP)          # two schedules forced at once
+    V2, Y2 = net.activate(wl.X, flags=WORKGROUP, use_workspace=False)      # needs no workspace
+    torch.cuda.synchronize()
+    assert torch.equal(V1, V2) and torch.equal(Y1, Y2)
+    for sched in SCHEDULES:
+        V3, _ = net.activate(wl.X, flags=sched | amd.FLAG_RAW_INPUTS)
+        net.check(wl.B)
+        want = oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.X, raw_inputs=True)
+        got = net.values_original_order(V3).cpu().numpy()
+        assert np.abs(got.astype(np.float64) - want).max() <= TIGHT
     V3, _ = net.activate(wl.X, flags=amd.FLAG_RAW_INPUTS)
     want = oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.X, raw_inputs=True)
     got = net.values_original_order(V3).cpu().numpy()
@@ -209,7 +220,7 @@ def test_saturation_gives_exact_zero_and_one(amd):
     src = np.zeros(8192, dtype=np.int32)
     dst = np.concatenate([np.full(4096, 1), np.full(4096, 2)]).astype(np.int32)
     w = np.concatenate([np.full(4096, -1.0), np.full(4096, 1.0)]).astype(np.float32)
-    for flags in (LEVELS, LEVELS | 2, DATAFLOW, DATAFLOW | 2):
+    for flags in (LEVELS, LEVELS | 2, DATAFLOW, DATAFLOW | 2, WORKGROUP, WORKGROUP | 2):
         wl = Workload("sat", 3, src, dst, w, np.array([0], np.int32), np.array([1, 2], np.int32),
                       np.zeros((1, 4), np.float32))
         _, V, Y = run_gpu(amd, wl, flags=flags)
@@ -218,7 +229,7 @@ def test_saturation_gives_exact_zero_and_one(amd):
     wl = Workload("sat2", 2, np.array([0], np.int32), np.array([1], np.int32), np.array([-1.0], np.float32),
                   np.array([0], np.int32), np.array([1], np.int32),
                   np.array([[30.0, 1000.0, 3.0e38, -3.0e38]], np.float32))
-    for flags in (LEVELS | 1, LEVELS | 3, DATAFLOW | 1, DATAFLOW | 3):
+    for flags in (LEVELS | 1, LEVELS | 3, DATAFLOW | 1, DATAFLOW | 3, WORKGROUP | 1, WORKGROUP | 3):
         _, V, Y = run_gpu(amd, wl, flags=flags)
         y = Y.cpu().numpy()[0]
         assert (y[:3] == 0.0).all() and y[3] == 1.0
@@ -230,7 +241,7 @@ def test_degenerate_networks(amd):
     wl = Workload("noedge", 3, np.zeros(0, np.int32), np.zeros(0, np.int32), np.zeros(0, np.float32),
                   np.array([2, 0], np.int32), np.array([1, 2], np.int32), np.array([[0.0, 1.0], [0.25, 0.5]], np.float32))
     want = oracle.activate(3, wl.src, wl.dst, wl.w, wl.input_ids, wl.X)
-    for sched in (0, LEVELS, DATAFLOW):
+    for sched in (0, LEVELS, DATAFLOW, WORKGROUP):
         net, V, Y = run_gpu(amd, wl, flags=sched)
         assert net.n_levels == 1
         got = net.values_original_order(V).cpu().numpy()
@@ -240,7 +251,7 @@ def test_degenerate_networks(amd):
                   np.array([1.0, -2.0, 0.5, 3.0], np.float32), np.array([0], np.int32), np.array([4], np.int32),
                   np.array([[0.3]], np.float32))
     want = oracle.activate(5, wl.src, wl.dst, wl.w, wl.input_ids, wl.X)
-    for sched in (0, LEVELS, DATAFLOW):
+    for sched in (0, LEVELS, DATAFLOW, WORKGROUP):
         net, V, Y = run_gpu(amd, wl, flags=sched)
         assert net.n_levels == 5
         assert np.abs(net.values_original_order(V).cpu().numpy() - want).max() <= TIGHT
@@ -281,7 +292,7 @@ FULL_COLUMNS = {1: None, 2: None, 3: 48, 4: 16, 5: 12}
 @pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
 def test_full_size_configs(amd, idx):
     """The five workloads at full size, in the default schedule (the one the
-    benchmark times) and in both forced schedules.  Levels: every node,
+    benchmark times) and in every forced schedule.  Levels: every node,
     bit-exact.  Activations: batch columns are independent, so the oracle
     evaluates a spread subset of columns (all nodes of those columns) and the
     same columns of the GPU result must agree."""
@@ -297,7 +308,7 @@ def test_full_size_configs(amd, idx):
     want = oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, np.ascontiguousarray(wl.X[:, cols]))
     inv = net.graph.inv_perm.long()
     tcols = torch.as_tensor(cols, device="cuda:0")
-    for sched in (0, LEVELS, DATAFLOW):
+    for sched in (0, LEVELS, DATAFLOW, WORKGROUP):
         _, V, Y = run_gpu(amd, wl, flags=sched, net=net)
         got = V[:, tcols][inv].cpu().numpy()
         assert np.isfinite(got).all()
@@ -392,8 +403,16 @@ def test_schedule_choice_is_reported(amd):
     assert amd.asnn_activate_schedule(g, wl.B, False, 0) == "levels"        # no workspace
     assert amd.asnn_activate_schedule(g, wl.B, True, LEVELS) == "levels"
     assert amd.asnn_activate_schedule(g, 1 << 20, True, 0) == "levels"      # big levels
+    assert amd.asnn_activate_schedule(g, wl.B, False, WORKGROUP) == "workgroup"
     with pytest.raises(amd.AsnnError):
         amd.asnn_activate_schedule(g, wl.B, False, DATAFLOW)
+    with pytest.raises(amd.AsnnError):
+        amd.asnn_activate_schedule(g, wl.B, True, LEVELS | WORKGROUP)
+    tiny = make_config(1, "full")           # a few hundred connections: one workgroup per tile by default
+    tnet = amd.Network(tiny.n_nodes, tiny.src, tiny.dst, tiny.w, tiny.input_ids, tiny.output_ids)
+    assert amd.asnn_activate_schedule(tnet.graph, 1, True, 0) == "workgroup"
+    assert amd.asnn_activate_schedule(tnet.graph, 8, False, 0) == "workgroup"
+    assert amd.asnn_activate_schedule(tnet.graph, 4096, False, 0) == "levels"       # wide batch: spread over the chip
 
 
 @pytest.mark.parametrize("idx,scale", [(1, "small"), (3, "small"), (4, "small"), (5, "small"), (3, "full")])
