@@ -68,7 +68,8 @@ extern "C" {
 /* In-degree classes.  Inside a level the packed order lists the heavy nodes
  * (in-degree >= ASNN_HEAVY_INDEGREE) first, then the medium ones
  * (>= ASNN_MEDIUM_INDEGREE), then the light ones (see asnn_pack_csr): the
- * activation gives a heavy row 16 wavefronts, a medium row 4, a light row 1. */
+ * activation gives a heavy row 16 wavefronts (and, in the dataflow schedule,
+ * several workgroups), a medium row 4 or 16, a light row 1. */
 #define ASNN_HEAVY_INDEGREE 256
 #define ASNN_MEDIUM_INDEGREE 32
 #define ASNN_CLASSES 3
@@ -141,6 +142,8 @@ typedef struct asnn_packed {
     int64_t n_edges;
     int32_t n_units;            /* out: number of work units (see unit_ptr) */
     int32_t first_unit;         /* out: first unit above level 0 */
+    int32_t max_heavy_indegree; /* out: largest in-degree among the heavy nodes (0 if there is none) */
+    int32_t reserved;           /* keeps the pointers 8-byte aligned; not used */
     int32_t *level_ptr_host;    /* host   int32[3*n_levels+1]: copy of level_ptr for the host */
     int32_t *level_ptr;         /* device int32[3*n_levels+1]: level l holds packed rows
                                    [level_ptr[3l], level_ptr[3l+1]) heavy, [.. 3l+1, 3l+2) medium, [.. 3l+2, 3l+3) light */
@@ -149,9 +152,13 @@ typedef struct asnn_packed {
     int32_t *row_ptr;           /* device int32[n_nodes+1] connections of packed row i are [row_ptr[i], row_ptr[i+1]) */
     int32_t *col;               /* device int32[n_edges]   packed row of the connection's source */
     float *w;                   /* device float[n_edges] */
-    int32_t *unit_ptr;          /* device int32[n_nodes+1] (n_units+1 used): unit u = packed rows
-                                   [unit_ptr[u], unit_ptr[u+1]), all of one level and class: 1 heavy row,
-                                   up to 4 medium rows or up to 16 light rows; units are in packed order */
+    int32_t *unit_ptr;          /* device int32[n_nodes + n_edges/512 + 2] (n_units+1 used).  Work units in
+                                   packed order, each inside one level and class: up to 8 light rows,
+                                   one medium row, or one heavy row or one chunk of it.  A heavy row
+                                   of in-degree d is cut into ceil(d/len) chunks of
+                                   len = max(512, ceil(d/16)) connections, one unit per chunk.
+                                   unit_ptr[u] = first packed row of unit u (the chunks of one row
+                                   repeat it), unit_ptr[n_units] = n_nodes */
 } asnn_packed;
 
 /*   src, dst, w  device            the connections, as for asnn_build_levels
@@ -171,10 +178,12 @@ int asnn_pack_csr(const int32_t *src, const int32_t *dst, const float *w, const 
  *   - level launches: one launch per level on the stream; the boundary
  *     between two launches is the paper's layer barrier;
  *   - dataflow: one persistent launch; workgroups claim work units in packed
- *     order and a row waits only for its own source rows (per-row ready
- *     flags), so a deep, narrow network is not paced by a barrier per layer
- *     (the paper names grid-wide synchronisation as future work).  Needs the
- *     workspace and n_nodes*B*4 < 4 GiB;
+ *     order and a row waits only for its own source rows (the value itself is
+ *     the ready flag), so a deep, narrow network is not paced by a barrier
+ *     per layer (the paper names grid-wide synchronisation as future work).
+ *     The chunks of a heavy row are gathered by different workgroups; their
+ *     partial sums meet in the workspace and are added in chunk order.  Needs
+ *     the workspace and n_nodes*B*4 < 4 GiB;
  *   - workgroup: the shape of the paper's kernel, one workgroup walks all
  *     levels with a workgroup barrier between two levels; batch columns are
  *     independent, so there is one such workgroup per tile of up to 64
@@ -195,14 +204,16 @@ int asnn_pack_csr(const int32_t *src, const int32_t *dst, const float *w, const 
  *   V           device float[n_nodes*B]  receives the activation of EVERY node, packed
  *               row order (row i = node perm[i]); 16-byte aligned
  *   Y           device float[n_outputs*B] or NULL; receives the rows of output_ids
- *   workspace   device, >= asnn_activate_workspace_bytes(n_nodes, B), 256-byte aligned,
- *               or NULL (level launches only).  Contents need not be preserved.
+ *   workspace   device, >= asnn_activate_workspace_bytes(packed, B), 256-byte aligned,
+ *               or NULL (no dataflow schedule then).  256 bytes, plus
+ *               n_edges*B/32 bytes (B rounded up to whole tiles) when a node has more
+ *               than 512 connections.  Contents need not be preserved.
  * Ids outside [0,n_nodes) in input_ids / output_ids are skipped (an output row
  * of such an id is filled with NaN).  Errors: NULL, SIZE, WORKSPACE, HIP.
  * Asynchronous.  A dataflow wait that exceeds its time limit (it cannot with
  * a valid packed record) stops waiting and raises a flag in the workspace
  * that asnn_activate_status reports. */
-size_t asnn_activate_workspace_bytes(int32_t n_nodes, int32_t B);
+size_t asnn_activate_workspace_bytes(const asnn_packed *packed, int32_t B);
 /* Which schedule asnn_activate takes for this record, batch width, workspace
  * (given or not) and flags: 0 = one launch per level, 1 = dataflow, 2 = one
  * workgroup per tile, < 0 = the error asnn_activate would return for this

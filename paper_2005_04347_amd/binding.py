@@ -86,7 +86,7 @@ def load() -> ctypes.CDLL:
     lib.asnn_pack_csr.restype = ctypes.c_int
     lib.asnn_pack_csr.argtypes = [vp, vp, vp, vp, ctypes.POINTER(AsnnPacked), vp, sz, vp]
     lib.asnn_activate_workspace_bytes.restype = sz
-    lib.asnn_activate_workspace_bytes.argtypes = [i32, i32]
+    lib.asnn_activate_workspace_bytes.argtypes = [ctypes.POINTER(AsnnPacked), i32]
     lib.asnn_activate.restype = ctypes.c_int
     lib.asnn_activate.argtypes = [ctypes.POINTER(AsnnPacked), vp, i32, vp, i32, vp, i32, vp, vp, vp, sz, u32, vp]
     lib.asnn_activate_schedule.restype = ctypes.c_int
@@ -182,6 +182,7 @@ class AsnnPacked(ctypes.Structure):
     _fields_ = [
         ("n_nodes", ctypes.c_int32), ("n_levels", ctypes.c_int32), ("n_edges", ctypes.c_int64),
         ("n_units", ctypes.c_int32), ("first_unit", ctypes.c_int32),
+        ("max_heavy_indegree", ctypes.c_int32), ("reserved", ctypes.c_int32),
         ("level_ptr_host", ctypes.c_void_p), ("level_ptr", ctypes.c_void_p), ("perm", ctypes.c_void_p),
         ("inv_perm", ctypes.c_void_p), ("row_ptr", ctypes.c_void_p), ("col", ctypes.c_void_p),
         ("w", ctypes.c_void_p), ("unit_ptr", ctypes.c_void_p),
@@ -200,7 +201,7 @@ class PackedGraph:
     row_ptr: torch.Tensor            # device int32 [n_nodes+1]
     col: torch.Tensor                # device int32 [n_edges]
     w: torch.Tensor                  # device float32 [n_edges]
-    unit_ptr: torch.Tensor           # device int32 [n_nodes+1], n_units+1 entries used
+    unit_ptr: torch.Tensor           # device int32 [n_nodes + n_edges//512 + 2], n_units+1 entries used
     n_units: int = 0
     first_unit: int = 0
     record: Optional[AsnnPacked] = None   # the C record (points into the tensors above)
@@ -218,7 +219,7 @@ def asnn_pack_csr(n_nodes: int, n_levels: int, src, dst, w, level) -> PackedGrap
     row_ptr = torch.empty(n_nodes + 1, dtype=torch.int32, device=device)
     col = torch.empty(max(n_edges, 1), dtype=torch.int32, device=device)
     wp = torch.empty(max(n_edges, 1), dtype=torch.float32, device=device)
-    unit_ptr = torch.empty(n_nodes + 1, dtype=torch.int32, device=device)
+    unit_ptr = torch.empty(n_nodes + n_edges // 512 + 2, dtype=torch.int32, device=device)
     ws = _workspace(lib.asnn_pack_workspace_bytes(n_nodes, n_edges), device)
     rec = AsnnPacked(n_nodes=n_nodes, n_levels=n_levels, n_edges=n_edges, n_units=0, first_unit=0,
                      level_ptr_host=level_ptr_host.ctypes.data, level_ptr=level_ptr.data_ptr(), perm=perm.data_ptr(),
@@ -235,7 +236,7 @@ def asnn_pack_csr(n_nodes: int, n_levels: int, src, dst, w, level) -> PackedGrap
 def asnn_activate_workspace(g: PackedGraph, B: int, device) -> torch.Tensor:
     """Device scratch for the dataflow schedule of asnn_activate (contents need not be preserved)."""
     lib = load()
-    return _workspace(lib.asnn_activate_workspace_bytes(g.n_nodes, B), device)
+    return _workspace(lib.asnn_activate_workspace_bytes(ctypes.byref(g.record), B), device)
 
 
 def asnn_activate(g: PackedGraph, input_ids: torch.Tensor, X: torch.Tensor,

@@ -287,6 +287,30 @@ __device__ inline bool shows_not_ready(const float (&v)[VEC]) {
     return r;
 }
 
+// Partial sums of the chunks of a split heavy row travel through the workspace in ACC precision,
+// marked "not written yet" the same way (for double: the pattern in the high word, zero below).
+template <typename ACC> struct PartialBits;
+template <> struct PartialBits<float> {
+    __device__ static inline float load(__amdgpu_buffer_rsrc_t r, uint32_t off, bool &ready) {
+        const unsigned int b = __builtin_amdgcn_raw_buffer_load_b32(r, off, 0, kAuxDeviceScope);
+        ready = b != kNotReady;
+        return __builtin_bit_cast(float, b);
+    }
+    __device__ static inline void store(__amdgpu_buffer_rsrc_t r, uint32_t off, float v) {
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, v), r, off, 0, kAuxDeviceScope);
+    }
+};
+template <> struct PartialBits<double> {
+    __device__ static inline double load(__amdgpu_buffer_rsrc_t r, uint32_t off, bool &ready) {
+        const uintx2 b = __builtin_amdgcn_raw_buffer_load_b64(r, off, 0, kAuxDeviceScope);
+        ready = b.y != kNotReady;
+        return __builtin_bit_cast(double, b);
+    }
+    __device__ static inline void store(__amdgpu_buffer_rsrc_t r, uint32_t off, double v) {
+        __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(uintx2, v), r, off, 0, kAuxDeviceScope);
+    }
+};
+
 // Bounded back-off between two attempts to read a tile that is not written yet.
 // Returns false when the wait must be abandoned (time limit, or another wave gave up).
 struct Patience {
@@ -401,13 +425,23 @@ __device__ inline void row_sum_dataflow(const int32_t *__restrict__ col, const f
     }
 }
 
-// Marks every value of rows [first_row, n_nodes) as not written and resets the control block.
-__global__ void dataflow_reset_kernel(unsigned int *v_begin, size_t n_values, DataflowCtl *ctl) {
+// Marks every value of rows [first_row, n_nodes) and every partial-sum word as not written and
+// resets the control block.  (For double partial sums every 32-bit word gets the pattern: the
+// high word is the one that is tested.)
+__global__ void dataflow_reset_kernel(unsigned int *v_begin, size_t n_values, unsigned int *partial_words,
+                                      size_t n_partial_words, DataflowCtl *ctl) {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_values; i += stride) v_begin[i] = kNotReady;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_partial_words; i += stride)
+        partial_words[i] = kNotReady;
     if (blockIdx.x == 0 && threadIdx.x < 64)
         reinterpret_cast<int *>(ctl)[threadIdx.x] = (threadIdx.x == 2) ? kCtlMagic : 0;
 }
+
+// Partial-sum slot of chunk 0 of a split heavy row whose connections start at e_begin: split rows
+// have more than kHeavyChunk connections and at most one chunk per kHeavyChunk of them, so
+// slots of kHeavyChunk/2 connections never collide between two rows.
+__host__ __device__ inline uint32_t partial_slot(int e_begin) { return (uint32_t)e_begin / (kHeavyChunk / 2); }
 
 template <int VEC, int LPG, typename ACC, int U>
 __global__ __launch_bounds__(kMixedBlock) void dataflow_kernel(const int32_t *__restrict__ row_ptr,
@@ -415,11 +449,12 @@ __global__ __launch_bounds__(kMixedBlock) void dataflow_kernel(const int32_t *__
                                                                 const float *__restrict__ w, float *V, uint32_t v_bytes,
                                                                 int B, const int32_t *__restrict__ unit_ptr,
                                                                 int first_unit, int n_work, int tiles, int first_row,
-                                                                DataflowCtl *ctl) {
+                                                                DataflowCtl *ctl, void *partials, uint32_t partial_bytes) {
     constexpr int T = LPG * VEC;
     __shared__ ACC part[kMixedWaves][LPG * VEC];
     __shared__ int s_claim;
     const __amdgpu_buffer_rsrc_t vres = __builtin_amdgcn_make_buffer_rsrc(V, 0, (int)v_bytes, kBufferFlags);
+    const __amdgpu_buffer_rsrc_t pres = __builtin_amdgcn_make_buffer_rsrc(partials, 0, (int)partial_bytes, kBufferFlags);
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
     const int lane = threadIdx.x & (kWave - 1);
     for (;;) {
@@ -432,19 +467,33 @@ __global__ __launch_bounds__(kMixedBlock) void dataflow_kernel(const int32_t *__
         const int u = first_unit + q / tiles;
         const int tile = q % tiles;
         const int r0 = unit_ptr[u], r1 = unit_ptr[u + 1];
-        const int d0 = row_ptr[r0 + 1] - row_ptr[r0];
-        const int share = d0 >= ASNN_HEAVY_INDEGREE ? kMixedWaves : (d0 >= ASNN_MEDIUM_INDEGREE ? kMediumWaves : 1);
+        const int row0_begin = row_ptr[r0], row0_end = row_ptr[r0 + 1];
+        const int d0 = row0_end - row0_begin;
+        const bool heavy = d0 >= ASNN_HEAVY_INDEGREE;
+        const int share = d0 >= ASNN_MEDIUM_INDEGREE ? kMixedWaves : 1;     // wavefronts on one row
+        // A heavy row may be cut into chunks, one unit each (consecutive units that name the same row).
+        const int n_chunks = heavy ? heavy_chunks(d0) : 1;
+        int chunk = 0;
+        if (n_chunks > 1) {
+#pragma unroll
+            for (int k = 1; k < kMaxHeavyChunks; ++k) chunk += (u - k >= 0 && unit_ptr[max(u - k, 0)] == r0) ? 1 : 0;
+        }
         const int row_try = r0 + wave / share;
-        const bool valid = row_try < r1;
+        const bool valid = heavy || row_try < r1;
         const int row = valid ? row_try : r0;
         const int slice = wave % share;
         const int c = tile * T + (lane % LPG) * VEC;
         const bool active = valid && c < B;
         ACC acc[VEC];
         if (valid) {
-            const int e0 = row_ptr[row], e1 = row_ptr[row + 1];
-            const int chunk = (e1 - e0 + share - 1) / share;
-            const int b0 = min(e0 + slice * chunk, e1), b1 = min(b0 + chunk, e1);
+            int e0 = row_ptr[row], e1 = row_ptr[row + 1];
+            if (n_chunks > 1) {
+                const int len = heavy_chunk_len(d0);
+                e0 = row0_begin + chunk * len;
+                e1 = min(e0 + len, row0_end);
+            }
+            const int per = (e1 - e0 + share - 1) / share;
+            const int b0 = min(e0 + slice * per, e1), b1 = min(b0 + per, e1);
             row_sum_dataflow<VEC, LPG, ACC, U>(col, w, vres, B, b0, b1, active ? c : 0, first_row, ctl, acc);
         } else {
 #pragma unroll
@@ -465,7 +514,49 @@ __global__ __launch_bounds__(kMixedBlock) void dataflow_kernel(const int32_t *__
                 }
             }
         }
-        if (active && slice == 0 && lane < LPG) {
+        if (n_chunks > 1 && wave == 0) {               // wave-uniform
+            // element (slot, tile, column) of the partial-sum area, in bytes
+            const uint32_t slot0 = partial_slot(row0_begin);
+            const uint32_t in_slot = (uint32_t)tile * T + (uint32_t)(lane % LPG) * VEC;
+            const uint32_t slot_elems = (uint32_t)tiles * T;
+            if (chunk < n_chunks - 1) {
+                // not the last chunk: hand the partial sum to the unit that holds the last one
+                if (lane < LPG) {
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j)
+                        PartialBits<ACC>::store(pres, (uint32_t)(((slot0 + chunk) * slot_elems + in_slot + j) * sizeof(ACC)), acc[j]);
+                }
+            } else {
+                // the last chunk adds the others in chunk order, then its own
+                ACC total[VEC];
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) total[j] = ACC(0);
+                Patience patience;
+                for (int k = 0; k < n_chunks - 1; ++k) {
+                    ACC p[VEC];
+                    for (;;) {
+                        bool ok = true;
+                        if (lane < LPG) {
+#pragma unroll
+                            for (int j = 0; j < VEC; ++j) {
+                                bool ready;
+                                p[j] = PartialBits<ACC>::load(pres, (uint32_t)(((slot0 + k) * slot_elems + in_slot + j) * sizeof(ACC)), ready);
+                                ok = ok && ready;
+                            }
+                        } else {
+#pragma unroll
+                            for (int j = 0; j < VEC; ++j) p[j] = ACC(0);
+                        }
+                        if (__all(ok) || !patience.again(ctl)) break;
+                    }
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) total[j] += p[j];
+                }
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) acc[j] = total[j] + acc[j];
+            }
+        }
+        if (active && slice == 0 && lane < LPG && chunk == n_chunks - 1) {
             float out[VEC];
 #pragma unroll
             for (int j = 0; j < VEC; ++j) out[j] = squash(acc[j]);
@@ -784,6 +875,8 @@ struct DataflowArgs {
     DataflowCtl *ctl;
     int cus;
     int units_per_level;     // average, for sizing the persistent grid
+    void *partials;          // partial sums of split heavy rows
+    uint32_t partial_bytes;
 };
 
 template <int VEC, int LPG, typename ACC>
@@ -806,7 +899,7 @@ int launch_dataflow(const LevelArgs &a, const DataflowArgs &d) {
     if (blocks < 1) return ASNN_OK;
     hipLaunchKernelGGL((dataflow_kernel<VEC, LPG, ACC, kUnroll>), dim3((unsigned)blocks), dim3(kMixedBlock), 0, a.s,
                        a.row_ptr, a.col, a.w, a.V, d.v_bytes, a.B, d.unit_ptr, d.first_unit, d.n_work, tiles, d.first_row,
-                       d.ctl);
+                       d.ctl, d.partials, d.partial_bytes);
     ASNN_HIP_TRY(hipGetLastError());
     return ASNN_OK;
 }
@@ -927,17 +1020,34 @@ inline int tiles_for(int B) {
     return (vecs + lpg - 1) / lpg;
 }
 
+// Batch width rounded up to whole tiles of the dataflow lane layout.
+inline int64_t padded_batch(int B) {
+    const int vec = vec_for(B, true);
+    const int vecs = B / vec;
+    int lpg = 1;
+    while (lpg < 64 && lpg < vecs) lpg <<= 1;
+    return (int64_t)((vecs + lpg - 1) / lpg) * lpg * vec;
+}
+
+// Workspace of the dataflow schedule: the control block, then (only when some row is cut into
+// chunks) one slot of padded_batch(B) partial sums per kHeavyChunk/2 connections.
 struct ActivateWorkspace {
     DataflowCtl *ctl;
+    unsigned int *partials;
+    size_t partial_bytes;
     size_t bytes;
 };
 
-inline ActivateWorkspace carve_activate(void *ws, int32_t n_nodes, int32_t B) {
-    (void)n_nodes;
-    (void)B;
+inline ActivateWorkspace carve_activate(void *ws, const asnn_packed *packed, int32_t B) {
     Carver c(ws);
     ActivateWorkspace w;
     w.ctl = c.take<DataflowCtl>(1);
+    w.partial_bytes = 0;
+    if (packed->max_heavy_indegree > kHeavyChunk) {
+        const size_t slots = (size_t)(packed->n_edges / (kHeavyChunk / 2)) + kMaxHeavyChunks + 1;
+        w.partial_bytes = slots * (size_t)padded_batch(B) * sizeof(double);
+    }
+    w.partials = c.take<unsigned int>(w.partial_bytes / sizeof(unsigned int) + 1);
     w.bytes = c.off;
     return w;
 }
@@ -971,8 +1081,9 @@ int choose_schedule(const asnn_packed *packed, int32_t B, bool has_workspace, ui
     const long long n_work = (long long)(packed->n_units - packed->first_unit) * tiles_for(B);
     const bool possible = has_workspace && packed->unit_ptr && n_levels > 1 && packed->n_units > 0 &&
                           packed->first_unit >= 0 && packed->first_unit <= packed->n_units &&
-                          packed->n_units <= n_nodes && n_work > 0 && n_work < 0x7fffffffLL &&
-                          (uint64_t)n_nodes * (uint64_t)B * 4u <= 0xffffffffull;
+                          n_work > 0 && n_work < 0x7fffffffLL &&
+                          (uint64_t)n_nodes * (uint64_t)B * 4u <= 0xffffffffull &&
+                          carve_activate(nullptr, packed, B).partial_bytes <= 0xffffffffull;
     const bool workgroup_possible = packed->level_ptr != nullptr && tiles_for_workgroup(B) <= 0x7fffffffLL;
     if (flags & ASNN_FLAG_WORKGROUP) return workgroup_possible ? 2 : ASNN_ERR_NULL;
     if (flags & ASNN_FLAG_DATAFLOW) {
@@ -994,9 +1105,9 @@ extern "C" int asnn_activate_schedule(const asnn_packed *packed, int32_t B, int 
     return choose_schedule(packed, B, has_workspace != 0, flags);
 }
 
-extern "C" size_t asnn_activate_workspace_bytes(int32_t n_nodes, int32_t B) {
-    if (n_nodes <= 0 || B <= 0) return 0;
-    return carve_activate(nullptr, n_nodes, B).bytes;
+extern "C" size_t asnn_activate_workspace_bytes(const asnn_packed *packed, int32_t B) {
+    if (!packed || packed->n_nodes <= 0 || packed->n_edges < 0 || B <= 0) return 0;
+    return carve_activate(nullptr, packed, B).bytes;
 }
 
 extern "C" int asnn_activate_status(const void *workspace, void *stream) {
@@ -1034,7 +1145,7 @@ extern "C" int asnn_activate(const asnn_packed *packed, const int32_t *input_ids
     const int tiles = tiles_for(B);
     const int first_row = n_levels > 1 ? level_ptr_host[ASNN_CLASSES] : n_nodes;
     const long long n_work = (long long)(packed->n_units - packed->first_unit) * tiles;
-    if (dataflow && (((uintptr_t)workspace & 255u) != 0 || workspace_bytes < asnn_activate_workspace_bytes(n_nodes, B)))
+    if (dataflow && (((uintptr_t)workspace & 255u) != 0 || workspace_bytes < asnn_activate_workspace_bytes(packed, B)))
         return ASNN_ERR_WORKSPACE;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -1074,14 +1185,16 @@ extern "C" int asnn_activate(const asnn_packed *packed, const int32_t *input_ids
             ASNN_HIP_TRY(hipGetDeviceProperties(&prop, dev));
             cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
         }
-        ActivateWorkspace ws = carve_activate(workspace, n_nodes, B);
+        ActivateWorkspace ws = carve_activate(workspace, packed, B);
         const size_t n_values = (size_t)(n_nodes - first_row) * (size_t)B;
         hipLaunchKernelGGL(dataflow_reset_kernel, dim3(blocks_for(n_values, 256 * 8, 4096)), dim3(256), 0, s,
-                           reinterpret_cast<unsigned int *>(V + (size_t)first_row * (size_t)B), n_values, ws.ctl);
+                           reinterpret_cast<unsigned int *>(V + (size_t)first_row * (size_t)B), n_values, ws.partials,
+                           ws.partial_bytes / sizeof(unsigned int), ws.ctl);
         ASNN_HIP_TRY(hipGetLastError());
         const int units_per_level = (packed->n_units - packed->first_unit + n_levels - 2) / (n_levels - 1);
         DataflowArgs d{packed->unit_ptr, packed->first_unit, (int)n_work, first_row,
-                       (uint32_t)((uint64_t)n_nodes * (uint64_t)B * 4u), ws.ctl, cus, units_per_level};
+                       (uint32_t)((uint64_t)n_nodes * (uint64_t)B * 4u), ws.ctl, cus, units_per_level,
+                       ws.partials, (uint32_t)ws.partial_bytes};
         ASNN_TRY(f32 ? launch_dataflow_any<float>(a, d) : launch_dataflow_any<double>(a, d));
     } else {
         for (int l = 1; l < n_levels; ++l) {

@@ -31,6 +31,29 @@ void set_last_hip_error(hipError_t e);
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
+// ---- work units ---------------------------------------------------------
+// Work units of the dataflow schedule, one 16-wavefront workgroup each.  A heavy row (in-degree
+// d >= ASNN_HEAVY_INDEGREE) is cut into chunks of its connections, one unit each, so that a row
+// with thousands of connections is gathered by several compute units at once instead of round
+// after round by one: at most kMaxHeavyChunks chunks of at least kHeavyChunk connections (512
+// is one gather round of a workgroup at 64 batch columns; 256 and 1024 both measured slower).
+// A medium row is a unit of its own (all 16 wavefronts on it), light rows go kLightUnitRows to
+// a unit, one wavefront each: a level's rows become ready together, and eight rows per compute
+// unit pull their sources through its L1 faster than sixteen.
+constexpr int kHeavyChunk = 512;
+constexpr int kMaxHeavyChunks = 16;
+constexpr int kMediumUnitRows = 1;
+constexpr int kLightUnitRows = 8;
+__host__ __device__ inline int heavy_chunk_len(int d) {
+    const int spread = (d + kMaxHeavyChunks - 1) / kMaxHeavyChunks;
+    return spread > kHeavyChunk ? spread : kHeavyChunk;
+}
+__host__ __device__ inline int heavy_chunks(int d) {
+    const int len = heavy_chunk_len(d);
+    const int n = (d + len - 1) / len;
+    return n > 0 ? n : 1;
+}
+
 // Carves 256-byte aligned pieces out of a caller-provided workspace.
 struct Carver {
     char *base;

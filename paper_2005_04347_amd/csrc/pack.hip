@@ -108,30 +108,41 @@ __global__ void gather_edges_kernel(const uint32_t *__restrict__ sorted_edge, co
 }
 
 
-// Work units: every (level, class) segment of packed rows is cut into groups
-// of 1 (heavy), 4 (medium) or 16 (light) rows.  seg_units[k] = groups of key k.
-__device__ __host__ inline int unit_rows_of_class(int cls) { return cls == 0 ? 1 : (cls == 1 ? 4 : 16); }
-
-__global__ void segment_units_kernel(const int32_t *__restrict__ level_ptr, int32_t n_keys,
-                                     int32_t *__restrict__ seg_units) {
-    const int k = blockIdx.x * blockDim.x + threadIdx.x;
-    if (k > n_keys) return;
-    if (k == n_keys) { seg_units[k] = 0; return; }
-    const int g = unit_rows_of_class(k % ASNN_CLASSES);
-    seg_units[k] = (level_ptr[k + 1] - level_ptr[k] + g - 1) / g;
+// Work units, in packed order: a heavy row gives one unit per chunk of its connections (see
+// heavy_chunks), a medium row one unit, light rows go eight to a unit; a unit never spans two
+// (level, class) segments.  row_units[i] = units that START at packed row i.
+__global__ void row_units_kernel(const uint32_t *__restrict__ sorted_keys, const int32_t *__restrict__ level_ptr,
+                                 const int32_t *__restrict__ packed_deg, int32_t n_nodes,
+                                 int32_t *__restrict__ row_units, int32_t *__restrict__ max_indegree) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i > n_nodes) return;
+    if (i == n_nodes) { row_units[i] = 0; return; }
+    const int k = (int)(sorted_keys[i] >> kRankBits);
+    const int cls = k % ASNN_CLASSES;
+    const int off = i - level_ptr[k];
+    int units;
+    if (cls == 0) atomicMax(max_indegree, packed_deg[i]);      // lighter rows cannot hold the maximum if a heavy one exists
+    if (cls == 0) units = heavy_chunks(packed_deg[i]);
+    else if (cls == 1) units = (off % kMediumUnitRows == 0) ? 1 : 0;
+    else units = (off % kLightUnitRows == 0) ? 1 : 0;
+    row_units[i] = units;
 }
 
-// unit_ptr[u] = first packed row of unit u; unit_ptr[n_units] = n_nodes.
-__global__ void unit_ptr_kernel(const uint32_t *__restrict__ sorted_keys, const int32_t *__restrict__ level_ptr,
-                                const int32_t *__restrict__ seg_unit_start, int32_t n_nodes, int32_t n_keys,
+// unit_ptr[u] = first packed row of unit u (the chunks of one heavy row repeat it);
+// unit_ptr[n_units] = n_nodes.  first_unit[i] = exclusive scan of row_units.
+__global__ void unit_ptr_kernel(const int32_t *__restrict__ first_unit, int32_t n_nodes,
                                 int32_t *__restrict__ unit_ptr) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i > n_nodes) return;
-    if (i == n_nodes) { unit_ptr[seg_unit_start[n_keys]] = n_nodes; return; }
-    const int k = (int)(sorted_keys[i] >> kRankBits);
-    const int g = unit_rows_of_class(k % ASNN_CLASSES);
-    const int off = i - level_ptr[k];
-    if (off % g == 0) unit_ptr[seg_unit_start[k] + off / g] = i;
+    if (i == n_nodes) { unit_ptr[first_unit[n_nodes]] = n_nodes; return; }
+    for (int u = first_unit[i]; u < first_unit[i + 1]; ++u) unit_ptr[u] = i;
+}
+
+// out[0] = first unit above level 0, out[1] = number of units (out[2] holds the largest heavy in-degree).
+__global__ void unit_counts_kernel(const int32_t *__restrict__ first_unit, const int32_t *__restrict__ level_ptr,
+                                   int32_t n_nodes, int32_t *__restrict__ out) {
+    out[0] = first_unit[level_ptr[ASNN_CLASSES]];
+    out[1] = first_unit[n_nodes];
 }
 
 }  // namespace
@@ -213,16 +224,18 @@ extern "C" int asnn_pack_csr(const int32_t *src, const int32_t *dst, const float
     ASNN_HIP_TRY(hipGetLastError());
     ASNN_TRY(exclusive_scan_i32(ws.packed_deg, row_ptr, n + 1, ws.tmp, s));
     // work units (uses the sorted node keys, so before the edge sort recycles the buffers)
-    hipLaunchKernelGGL(segment_units_kernel, dim3(blocks_for((size_t)n_keys + 1, kThreads)), dim3(kThreads), 0, s,
-                       (const int32_t *)level_ptr, n_keys, ws.seg_units);
+    hipLaunchKernelGGL(row_units_kernel, dim3(blocks_for(n + 1, kThreads)), dim3(kThreads), 0, s, (const uint32_t *)ks,
+                       (const int32_t *)level_ptr, (const int32_t *)ws.packed_deg, n_nodes, ws.seg_units, ws.err + 4);
     ASNN_HIP_TRY(hipGetLastError());
-    ASNN_TRY(exclusive_scan_i32(ws.seg_units, ws.seg_units, (size_t)n_keys + 1, ws.tmp, s));
-    hipLaunchKernelGGL(unit_ptr_kernel, dim3(blocks_for(n + 1, kThreads)), dim3(kThreads), 0, s, (const uint32_t *)ks,
-                       (const int32_t *)level_ptr, (const int32_t *)ws.seg_units, n_nodes, n_keys, unit_ptr);
+    ASNN_TRY(exclusive_scan_i32(ws.seg_units, ws.seg_units, n + 1, ws.tmp, s));
+    hipLaunchKernelGGL(unit_ptr_kernel, dim3(blocks_for(n + 1, kThreads)), dim3(kThreads), 0, s,
+                       (const int32_t *)ws.seg_units, n_nodes, unit_ptr);
     ASNN_HIP_TRY(hipGetLastError());
-    int32_t host_units[2] = {0, 0};      // {first unit above level 0, number of units}
-    ASNN_HIP_TRY(hipMemcpyAsync(&host_units[0], ws.seg_units + ASNN_CLASSES, sizeof(int32_t), hipMemcpyDeviceToHost, s));
-    ASNN_HIP_TRY(hipMemcpyAsync(&host_units[1], ws.seg_units + n_keys, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    int32_t host_units[3] = {0, 0, 0};   // {first unit above level 0, number of units, largest heavy in-degree}
+    hipLaunchKernelGGL(unit_counts_kernel, dim3(1), dim3(1), 0, s, (const int32_t *)ws.seg_units,
+                       (const int32_t *)level_ptr, n_nodes, ws.err + 2);
+    ASNN_HIP_TRY(hipGetLastError());
+    ASNN_HIP_TRY(hipMemcpyAsync(host_units, ws.err + 2, 3 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
 
     // edges: stable sort by packed destination keeps each node's edge-list order
     if (n_edges > 0) {
@@ -243,5 +256,6 @@ extern "C" int asnn_pack_csr(const int32_t *src, const int32_t *dst, const float
     ASNN_HIP_TRY(hipStreamSynchronize(s));
     packed->first_unit = host_units[0];
     packed->n_units = host_units[1];
+    packed->max_heavy_indegree = host_units[2];
     return host_err;
 }

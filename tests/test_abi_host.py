@@ -119,9 +119,14 @@ def test_argument_checks_need_no_device(lib):
     assert act(rec(), flags=8) == -1                          # dataflow forced without a workspace
     assert act(rec(), flags=4 | 16) == -2 and act(rec(), flags=8 | 16) == -2
     assert act(rec(null=("level_ptr",)), flags=16) == -1      # the workgroup schedule reads the device level table
-    assert lib.asnn_activate_workspace_bytes(0, 4) == 0
-    nbytes = lib.asnn_activate_workspace_bytes(1000, 64)
+    assert lib.asnn_activate_workspace_bytes(None, 4) == 0
+    assert lib.asnn_activate_workspace_bytes(ctypes.byref(rec(n=0)), 4) == 0
+    nbytes = lib.asnn_activate_workspace_bytes(ctypes.byref(rec(n=1000, e=16000)), 64)
     assert 0 < nbytes <= 4096 and nbytes % 256 == 0
+    # a node with more than 512 connections is gathered in chunks whose partial sums pass through the workspace
+    r = rec(n=1000, e=16000)
+    r.max_heavy_indegree = 4096
+    assert lib.asnn_activate_workspace_bytes(ctypes.byref(r), 64) >= 16000 * 64 // 32
 
 
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):

@@ -64,15 +64,22 @@ def run_gpu(amd, wl, flags=0, poison=True, X=None, net=None):
     return net, V, Y
 
 
-def expected_units(level_ptr, n_levels):
-    """numpy statement of the work units: every (level, class) segment cut into groups of 1 / 4 / 16 rows."""
+def expected_units(level_ptr, n_levels, row_ptr):
+    """numpy statement of the work units: light rows in groups of 8 (never across a level
+    boundary), a medium row alone, a heavy row of in-degree d in ceil(d / len) chunks of
+    len = max(512, ceil(d / 16)) connections, one unit each, all naming the row."""
     starts = []
     first_unit = None
     for k in range(3 * n_levels):
         if k == 3:
             first_unit = len(starts)
-        g = (1, 4, 16)[k % 3]
-        starts += list(range(level_ptr[k], level_ptr[k + 1], g))
+        if k % 3 == 0:
+            for r in range(level_ptr[k], level_ptr[k + 1]):
+                d = int(row_ptr[r + 1] - row_ptr[r])
+                length = max(512, -(-d // 16))
+                starts += [r] * max(1, -(-d // length))
+        else:
+            starts += list(range(level_ptr[k], level_ptr[k + 1], (1, 1, 8)[k % 3]))
     if first_unit is None:
         first_unit = len(starts)
     return np.array(starts + [level_ptr[-1]], dtype=np.int32), first_unit
@@ -97,7 +104,7 @@ def test_small_configs_levels_pack_activation(amd, idx):
     assert (g.row_ptr.cpu().numpy() == row_ptr).all()
     assert (g.col.cpu().numpy() == col).all()
     assert (g.w.cpu().numpy() == w).all()
-    units, first_unit = expected_units(level_ptr, nl_o)
+    units, first_unit = expected_units(level_ptr, nl_o, row_ptr)
     assert g.n_units == len(units) - 1 and g.first_unit == first_unit
     assert (g.unit_ptr.cpu().numpy()[: g.n_units + 1] == units).all()
     want = oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.X)
@@ -146,7 +153,7 @@ def _heavy_workload(B, seed=3):
     root = n_in                      # zero in-degree, not a sensor
     src, dst = [], []
     for m in range(n_mid):
-        d = [1, 7, 31, 32, 33, 100, 255, 256, 257, 900, 4096, 5000][m % 12]
+        d = [1, 7, 31, 32, 33, 100, 255, 256, 257, 512, 513, 900, 4096, 5000, 20000][m % 15]
         src += rng.integers(0, n_in + 1, size=d).tolist()
         dst += [n_in + 1 + m] * d
     for t in range(3):
@@ -173,6 +180,11 @@ def test_heavy_rows_and_non_sensor_root(amd, B):
         lp = net.graph.level_ptr_host
         assert lp[4] - lp[3] > 0 and lp[7] - lp[6] > 0          # heavy ranges of levels 1 and 2 are populated
         assert lp[5] - lp[4] > 0 and lp[6] - lp[5] > 0          # and so are the medium and light ones of level 1
+        g = net.graph
+        units, first_unit = expected_units(lp, net.n_levels, g.row_ptr.cpu().numpy())     # rows cut into 2 .. 16 chunks
+        assert g.n_units == len(units) - 1 and g.first_unit == first_unit
+        assert (g.unit_ptr.cpu().numpy()[: g.n_units + 1] == units).all()
+        assert g.record.max_heavy_indegree == 20000
         got = net.values_original_order(V).cpu().numpy()
         assert (got[root] == np.float32(0.5)).all()
         err = float(np.abs(got.astype(np.float64) - want).max())
