@@ -318,7 +318,7 @@ struct Patience {
     int spins = 0;
     __device__ inline bool again(DataflowCtl *ctl) {
         if (spins == 0) t0 = wall_clock64();
-        __builtin_amdgcn_s_sleep(2);
+        __builtin_amdgcn_s_sleep(1);
         if ((++spins & 63) == 0) {
             const int err = __hip_atomic_load(&ctl->error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (err != 0 || wall_clock64() - t0 > kWaitTicks) {

@@ -459,3 +459,26 @@ def test_required_set_and_filtered_activation(amd, idx, scale):
     with pytest.raises(amd.AsnnError) as e:
         amd.asnn_required_set(wl.n_nodes, src, dst, torch.tensor([wl.n_nodes], dtype=torch.int32, device=dev))
     assert e.value.code == -3
+
+
+@pytest.mark.parametrize("idx", [3, 4, 5])
+def test_teacher_forced_single_level_error(amd, idx):
+    """Every node computed from the ORACLE's values of its sources (one hop), so the error of one
+    weighted sum + sigmoid is seen without the amplification along the levels: the end-to-end
+    error of the fp32 fast mode on deep networks is amplification of a per-node error of a few
+    1e-7, not a kernel defect.  The forced network has 2N nodes: node i carries the oracle's
+    value of node i as a raw sensor input, node N+j receives the connections of node j."""
+    from workloads import Workload
+    wl = make_config(idx, "small")
+    want = oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.X)      # float64 holding fp32 values
+    n = wl.n_nodes
+    has_in = np.bincount(wl.dst, minlength=n) > 0
+    forced = Workload("forced", 2 * n, wl.src, (wl.dst + n).astype(np.int32), wl.w, np.arange(n, dtype=np.int32),
+                      (np.nonzero(has_in)[0] + n).astype(np.int32), want.astype(np.float32))
+    net = None
+    for sched in SCHEDULES:
+        for fast, bound in ((0, 6.0e-8), (amd.FLAG_ACC_F32, 2.0e-6)):
+            net, V, Y = run_gpu(amd, forced, flags=sched | fast | amd.FLAG_RAW_INPUTS, net=net)
+            err = float(np.abs(Y.cpu().numpy().astype(np.float64) - want[has_in]).max())
+            print(f"config {idx} small, schedule {sched}, fp32 sums {bool(fast)}: single-level max_abs_err {err:.2e}")
+            assert err <= bound, (sched, fast, err)
