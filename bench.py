@@ -37,10 +37,11 @@ def algorithmic_bytes(n_nodes, n_edges, n_inputs, B):
 def measured_traffic(config, flags):
     """HBM bytes per level launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary of this
     workload (counter runs cannot be made from inside this process); None when no summary covers it."""
-    path = os.path.join(ROOT, "profiles", f"gather_kernel_config{config}_hbm_traffic.md")
-    if flags != 0 or not os.path.exists(path):
+    import glob
+    paths = glob.glob(os.path.join(ROOT, "profiles", f"*_config{config}_hbm_traffic.md"))
+    if flags != 0 or not paths:
         return None
-    for line in open(path):
+    for line in open(paths[0]):
         if line.startswith("traffic_bytes_per_launch:"):
             return float(line.split(":")[1])
     return None
@@ -104,8 +105,8 @@ def paper_regime(flags=0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--flags", type=int, default=0, help="asnn_activate flags (2 = fp32 accumulate)")
     ap.add_argument("--schedule", choices=["auto", "levels", "dataflow", "workgroup"], default="auto",
@@ -203,9 +204,9 @@ def main():
     alg_bytes = algorithmic_bytes(wl.n_nodes, wl.n_edges, len(wl.input_ids), B)
     achieved = alg_bytes / (dev_ms_med * 1e-3) / 1e9
     taken = amd.asnn_activate_schedule(net.graph, B, True, flags)
-    # level launches: one gather launch per level above the input level; dataflow: one persistent launch
-    launches = 1 if taken == "dataflow" else max(net.n_levels - 1, 1)
-    traffic = measured_traffic(args.config, args.flags)
+    # level launches: one gather launch per level above the input level; the other schedules: one launch
+    launches = max(net.n_levels - 1, 1) if taken == "levels" else 1
+    traffic = measured_traffic(args.config, args.flags) if args.schedule == "auto" and not args.graph else None
     out = {
         "metric": "G edge*samples/s for full ASNN activation",
         "value": round(value, 3),
@@ -224,8 +225,9 @@ def main():
                    "preprocess_ms_first_call": round(prep_ms, 2)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
-                     "kernel": ("dataflow_kernel (one persistent launch)" if taken == "dataflow" else
-                                "gather_light_kernel / gather_mixed_kernel (one launch per level)"),
+                     "kernel": {"dataflow": "dataflow_kernel (one persistent launch)",
+                                "workgroup": "workgroup_kernel (one launch, one workgroup per batch tile)",
+                                "levels": "gather_light_kernel / gather_mixed_kernel (one launch per level)"}[taken],
                      "launches_per_step": launches,
                      "algorithmic_bytes_per_launch": alg_bytes / launches,
                      "avg_launch_us": round(dev_ms_med * 1e3 / launches, 3),

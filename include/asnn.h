@@ -192,7 +192,7 @@ int asnn_pack_csr(const int32_t *src, const int32_t *dst, const float *w, const 
  *     launch.  Meant for small networks and narrow batches (the paper's own
  *     regime: one input vector, thousands of connections), where launches
  *     and level hand-overs cost more than the connections.
- * By default: the workgroup schedule up to n_edges*B = 32768; else the
+ * By default: the workgroup schedule up to n_edges*B = 13000 + 1300*n_levels; else the
  * dataflow schedule when a workspace is given and the average level is small;
  * else level launches.  ASNN_FLAG_LEVEL_LAUNCHES / ASNN_FLAG_DATAFLOW /
  * ASNN_FLAG_WORKGROUP force one (more than one of them: SIZE).

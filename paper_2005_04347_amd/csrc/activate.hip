@@ -1061,11 +1061,12 @@ int choose_schedule(const asnn_packed *packed, int32_t B, bool has_workspace, ui
 // about 8 us however little it does).
 constexpr double kDataflowMaxLevelWork = 8.0e6;
 // Connections*samples up to which one workgroup per tile beats the schedules that spread a
-// level over the chip: it pays under a microsecond per level and a single launch, but a
-// workgroup has few rows in flight, so beyond a narrow batch of a small network the
-// other schedules win (measured on MI355X: 16k connections at B = 1 take 24 us against
-// 30 us, at B = 8 41 us against 32 us).
-constexpr int64_t kWorkgroupMaxWork = 32768;
+// level over the chip.  Measured on MI355X at B = 1: the workgroup schedule takes about
+// 12 us + 0.8 us per level + 0.6 ns per connection, the dataflow schedule about
+// 20 us + 1.6 us per level and next to nothing per connection, so the break-even grows
+// with the depth (20k connections at 5 levels, 66k at 40).
+constexpr int64_t kWorkgroupBaseWork = 13000;
+constexpr int64_t kWorkgroupWorkPerLevel = 1300;
 
 }  // namespace
 }  // namespace asnn
@@ -1092,7 +1093,7 @@ int choose_schedule(const asnn_packed *packed, int32_t B, bool has_workspace, ui
         return possible ? 1 : 0;
     }
     if (flags & ASNN_FLAG_LEVEL_LAUNCHES) return 0;
-    if (workgroup_possible && packed->n_edges * (int64_t)B <= kWorkgroupMaxWork) return 2;
+    if (workgroup_possible && packed->n_edges * (int64_t)B <= kWorkgroupBaseWork + kWorkgroupWorkPerLevel * n_levels) return 2;
     if (!possible) return 0;
     return (double)packed->n_edges * (double)B / (double)(n_levels - 1) < kDataflowMaxLevelWork ? 1 : 0;
 }
