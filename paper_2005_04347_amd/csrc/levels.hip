@@ -17,12 +17,14 @@ constexpr int kThreads = 256;
 constexpr int kSweepsPerSync = 64;     // frontier sweeps enqueued between two host reads
 constexpr int kGroup = 16;             // lanes that share one frontier node's out-edges
 constexpr unsigned kSweepBlocks = 512;
+constexpr int kAggregateIndegree = 1024;   // networks with a node this heavy aggregate their releases per workgroup
 
 // Slots of the small control block in device memory.
 enum Ctl : int {
     kErr = 0,          // first error code seen (0 = none)
     kAssigned = 1,     // nodes that received a level so far
     kLevels = 2,       // number of non-empty frontiers so far
+    kMaxIndeg = 3,     // largest in-degree of the network
     kCount0 = 4,       // three rotating frontier sizes: sweep k reads kCount0 + k % 3
     kCtlInts = 16
 };
@@ -84,20 +86,41 @@ __global__ void fill_out_kernel(const int32_t *__restrict__ src, const int32_t *
 __global__ void first_frontier_kernel(int32_t n_nodes, const int32_t *__restrict__ indeg, int32_t *__restrict__ level,
                                       int32_t *__restrict__ frontier, int *ctl) {
     const int v = blockIdx.x * blockDim.x + threadIdx.x;
-    const bool root = v < n_nodes && indeg[v] == 0;
+    const int32_t d = v < n_nodes ? indeg[v] : 0;
+    const bool root = v < n_nodes && d == 0;
     if (v < n_nodes) level[v] = root ? 0 : -1;
     wave_append(root, v, frontier, &ctl[kCount0]);
+    int32_t m = d;                                   // largest in-degree: one atomic per wavefront that can raise it
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) m = max(m, __shfl_xor(m, off, kWave));
+    if ((threadIdx.x & (kWave - 1)) == 0 && m >= kAggregateIndegree) atomicMax(&ctl[kMaxIndeg], m);
 }
 
 // One sweep: every node of frontier k releases its out-edges; a destination
 // whose remaining in-degree drops to zero gets level k+1 and joins frontier k+1.
 // A sweep over an empty frontier does nothing, so the host may enqueue more
 // sweeps than the network has layers.
+//
+// 16 lanes share one frontier node's out-edges.  When the network holds a node
+// with thousands of incoming connections, that node receives thousands of
+// returning atomics on one address per sweep, which serialise (on a 1000-layer
+// network whose layers each hold such a node that was more than half of the
+// sweep time).  Such networks take the aggregating path: a workgroup handles
+// 16 frontier nodes at a time and first adds up its releases per destination
+// in a small LDS hash table, so a destination is decremented once per
+// workgroup and round, by the number of connections the workgroup's nodes send
+// it.  The path costs three workgroup barriers per round, so networks without
+// heavy nodes (every wavefront on its own, no barrier) do not take it.
+constexpr int kSweepSlots = 2 * kThreads;      // hash slots per workgroup: at most kThreads insertions per round
+
 __global__ __launch_bounds__(kThreads) void sweep_kernel(int k, const int32_t *__restrict__ out_ptr,
                                                           const int32_t *__restrict__ out_dst, int32_t *indeg,
                                                           int32_t *__restrict__ level,
                                                           const int32_t *__restrict__ frontier_in,
                                                           int32_t *__restrict__ frontier_out, int *ctl) {
+    __shared__ int32_t slot_node[kSweepSlots];
+    __shared__ int32_t slot_count[kSweepSlots];
+    __shared__ int32_t s_rounds;
     const int count = ctl[kCount0 + k % 3];
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         ctl[kCount0 + (k + 2) % 3] = 0;          // read by sweep k-1 (finished), filled by sweep k+1
@@ -108,16 +131,61 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(int k, const int32_t *_
     }
     if (count == 0) return;
     int *count_out = &ctl[kCount0 + (k + 1) % 3];
+    constexpr int kNodesPerBlock = kThreads / kGroup;
     const int sub = threadIdx.x % kGroup;
-    const int groups = gridDim.x * (kThreads / kGroup);
-    for (int f = blockIdx.x * (kThreads / kGroup) + threadIdx.x / kGroup; f < count; f += groups) {
-        const int32_t v = frontier_in[f];
-        const int32_t e1 = out_ptr[v + 1];
-        for (int32_t e = out_ptr[v] + sub; e < e1; e += kGroup) {
-            const int32_t u = out_dst[e];
-            const bool last = atomicSub(&indeg[u], 1) == 1;
-            if (last) level[u] = k + 1;
-            wave_append(last, u, frontier_out, count_out);
+    const int stride = gridDim.x * kNodesPerBlock;
+    if (ctl[kMaxIndeg] < kAggregateIndegree) {       // grid-uniform
+        for (int f = blockIdx.x * kNodesPerBlock + threadIdx.x / kGroup; f < count; f += stride) {
+            const int32_t v = frontier_in[f];
+            const int32_t e1 = out_ptr[v + 1];
+            for (int32_t e = out_ptr[v] + sub; e < e1; e += kGroup) {
+                const int32_t u = out_dst[e];
+                const bool last = atomicSub(&indeg[u], 1) == 1;
+                if (last) level[u] = k + 1;
+                wave_append(last, u, frontier_out, count_out);
+            }
+        }
+        return;
+    }
+    for (int base = blockIdx.x * kNodesPerBlock; base < count; base += stride) {      // block-uniform
+        const int f = base + threadIdx.x / kGroup;
+        int32_t e0 = 0, e1 = 0;
+        if (f < count) {
+            const int32_t v = frontier_in[f];
+            e0 = out_ptr[v];
+            e1 = out_ptr[v + 1];
+        }
+        if (threadIdx.x == 0) s_rounds = 0;
+        __syncthreads();
+        if (sub == 0 && e1 > e0) atomicMax(&s_rounds, (e1 - e0 + kGroup - 1) / kGroup);
+        __syncthreads();
+        const int rounds = s_rounds;             // block-uniform: rounds of one out-edge per lane
+        for (int r = 0; r < rounds; ++r) {
+            for (int i = threadIdx.x; i < kSweepSlots; i += kThreads) { slot_node[i] = -1; slot_count[i] = 0; }
+            __syncthreads();
+            const int32_t e = e0 + r * kGroup + sub;
+            if (e < e1) {
+                const int32_t u = out_dst[e];
+                unsigned h = ((unsigned)u * 2654435761u) >> 7;
+                for (;;) {                       // at most kThreads keys in 2*kThreads slots: a free slot exists
+                    h &= (unsigned)(kSweepSlots - 1);
+                    const int32_t seen = atomicCAS(&slot_node[h], -1, u);
+                    if (seen == -1 || seen == u) { atomicAdd(&slot_count[h], 1); break; }
+                    ++h;
+                }
+            }
+            __syncthreads();
+            for (int i = threadIdx.x; i < kSweepSlots; i += kThreads) {     // every thread: the same trip count
+                const int32_t u = slot_node[i];
+                bool last = false;
+                if (u >= 0) {
+                    const int32_t c = slot_count[i];
+                    last = atomicSub(&indeg[u], c) == c;
+                    if (last) level[u] = k + 1;
+                }
+                wave_append(last, u, frontier_out, count_out);
+            }
+            __syncthreads();
         }
     }
 }
