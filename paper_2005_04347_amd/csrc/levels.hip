@@ -112,6 +112,7 @@ __global__ void first_frontier_kernel(int32_t n_nodes, const int32_t *__restrict
 // it.  The path costs three workgroup barriers per round, so networks without
 // heavy nodes (every wavefront on its own, no barrier) do not take it.
 constexpr int kSweepSlots = 2 * kThreads;      // hash slots per workgroup: at most kThreads insertions per round
+constexpr int kFoundCap = 2048;                // next-frontier nodes a workgroup collects in LDS before appending
 
 __global__ __launch_bounds__(kThreads) void sweep_kernel(int k, const int32_t *__restrict__ out_ptr,
                                                           const int32_t *__restrict__ out_dst, int32_t *indeg,
@@ -135,16 +136,32 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(int k, const int32_t *_
     const int sub = threadIdx.x % kGroup;
     const int stride = gridDim.x * kNodesPerBlock;
     if (ctl[kMaxIndeg] < kAggregateIndegree) {       // grid-uniform
+        // The nodes this workgroup adds to the next frontier are collected in LDS and appended
+        // with ONE atomic on the frontier size: with tens of thousands of nodes per frontier,
+        // one atomic per wavefront on that single address was most of the sweep time.
+        __shared__ int32_t found[kFoundCap];
+        __shared__ int n_found, found_base;
+        if (threadIdx.x == 0) n_found = 0;
+        __syncthreads();
         for (int f = blockIdx.x * kNodesPerBlock + threadIdx.x / kGroup; f < count; f += stride) {
             const int32_t v = frontier_in[f];
             const int32_t e1 = out_ptr[v + 1];
             for (int32_t e = out_ptr[v] + sub; e < e1; e += kGroup) {
                 const int32_t u = out_dst[e];
                 const bool last = atomicSub(&indeg[u], 1) == 1;
-                if (last) level[u] = k + 1;
-                wave_append(last, u, frontier_out, count_out);
+                if (last) {
+                    level[u] = k + 1;
+                    const int pos = atomicAdd(&n_found, 1);                  // LDS
+                    if (pos < kFoundCap) found[pos] = u;
+                    else frontier_out[atomicAdd(count_out, 1)] = u;          // LDS list full: append directly
+                }
             }
         }
+        __syncthreads();
+        const int n = min(n_found, kFoundCap);
+        if (threadIdx.x == 0 && n > 0) found_base = atomicAdd(count_out, n);
+        __syncthreads();
+        for (int i = threadIdx.x; i < n; i += kThreads) frontier_out[found_base + i] = found[i];
         return;
     }
     for (int base = blockIdx.x * kNodesPerBlock; base < count; base += stride) {      // block-uniform
@@ -321,15 +338,28 @@ __global__ __launch_bounds__(kThreads) void reach_sweep_kernel(int k, const int3
     int *count_out = &ctl[kCount0 + (k + 1) % 3];
     const int sub = threadIdx.x % kGroup;
     const int groups = gridDim.x * (kThreads / kGroup);
+    // newly reached nodes are collected per workgroup and appended with one atomic (see sweep_kernel)
+    __shared__ int32_t found[kFoundCap];
+    __shared__ int n_found, found_base;
+    if (threadIdx.x == 0) n_found = 0;
+    __syncthreads();
     for (int f = blockIdx.x * (kThreads / kGroup) + threadIdx.x / kGroup; f < count; f += groups) {
         const int32_t v = frontier_in[f];
         const int32_t e1 = in_ptr[v + 1];
         for (int32_t e = in_ptr[v] + sub; e < e1; e += kGroup) {
             const int32_t a = in_src[e];
-            const bool first = atomicExch(&required[a], 1) == 0;
-            wave_append(first, a, frontier_out, count_out);
+            if (atomicExch(&required[a], 1) == 0) {
+                const int pos = atomicAdd(&n_found, 1);                  // LDS
+                if (pos < kFoundCap) found[pos] = a;
+                else frontier_out[atomicAdd(count_out, 1)] = a;
+            }
         }
     }
+    __syncthreads();
+    const int n = min(n_found, kFoundCap);
+    if (threadIdx.x == 0 && n > 0) found_base = atomicAdd(count_out, n);
+    __syncthreads();
+    for (int i = threadIdx.x; i < n; i += kThreads) frontier_out[found_base + i] = found[i];
 }
 
 __global__ void keep_flag_kernel(const int32_t *__restrict__ src, const int32_t *__restrict__ dst,
