@@ -59,47 +59,49 @@ def paper_regime(flags=0):
     from workloads import layered_skip
 
     amd.load()
-    for n_levels in (5, 40):
-        for n_edges in (1000, 2000, 4000, 8000, 16000, 30000, 70000, 150000, 300000):
-            n_nodes = max(n_edges // 10, 3 * n_levels)
-            n_io = max(4, n_nodes // 50)
-            wl = layered_skip(seed=1, n_nodes=n_nodes, n_inputs=n_io, n_outputs=n_io, n_levels=n_levels, B=1,
-                              mean_extra_degree=n_edges / (n_nodes - n_io) - 1.0)
-            net = amd.Network(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.output_ids)
-            X = torch.from_numpy(wl.X).cuda()
-            V = torch.empty((wl.n_nodes, 1), device="cuda")
-            Y = torch.empty((len(wl.output_ids), 1), device="cuda")
-            for _ in range(5):
-                net.activate(X, V=V, Y=Y, flags=flags)
-            torch.cuda.synchronize()
-            # resident: events around 10 activations; with transfers: host X in, host Y out, as the paper timed it
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(10):
-                net.activate(X, V=V, Y=Y, flags=flags)
-            e1.record()
-            torch.cuda.synchronize()
-            gpu_us = e0.elapsed_time(e1) * 1e3 / 10
-            t0 = time.perf_counter()
-            for _ in range(10):
-                Xd = torch.from_numpy(wl.X).cuda()
-                net.activate(Xd, V=V, Y=Y, flags=flags)
-                y_host = Y.cpu()
-            copy_us = (time.perf_counter() - t0) * 1e6 / 10
-            oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.X)
-            cpu_us = 0.0
-            for _ in range(5):          # the node loop only: the paper times activation after its preprocessing
-                tm = {}
-                ref = oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.X, timing=tm)
-                cpu_us += tm["activation_seconds"] * 1e6 / 5
-            err = float(np.abs(net.values_original_order(V).cpu().numpy().astype(np.float64) - ref).max())
-            print(json.dumps({"regime": "paper: batch 1", "connections": wl.n_edges, "nodes": wl.n_nodes,
-                              "levels": net.n_levels,
-                              "schedule_taken": amd.asnn_activate_schedule(net.graph, 1, True, flags),
-                              "gpu_us_resident": round(gpu_us, 1),
-                              "gpu_us_with_host_copies": round(copy_us, 1), "cpu_oracle_us": round(cpu_us, 1),
-                              "speedup_resident": round(cpu_us / gpu_us, 2),
-                              "speedup_with_host_copies": round(cpu_us / copy_us, 2), "max_abs_err": err}), flush=True)
+    # connections swept at two depths, then depth swept at a fixed number of connections
+    sweep = [(L, E) for L in (5, 40) for E in (1000, 2000, 4000, 8000, 16000, 30000, 70000, 150000, 300000)]
+    sweep += [(L, 16000) for L in (3, 10, 20, 80, 160)]
+    for n_levels, n_edges in sweep:
+        n_nodes = max(n_edges // 10, 3 * n_levels)
+        n_io = max(4, n_nodes // 50)
+        wl = layered_skip(seed=1, n_nodes=n_nodes, n_inputs=n_io, n_outputs=n_io, n_levels=n_levels, B=1,
+                          mean_extra_degree=n_edges / (n_nodes - n_io) - 1.0)
+        net = amd.Network(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.output_ids)
+        X = torch.from_numpy(wl.X).cuda()
+        V = torch.empty((wl.n_nodes, 1), device="cuda")
+        Y = torch.empty((len(wl.output_ids), 1), device="cuda")
+        for _ in range(5):
+            net.activate(X, V=V, Y=Y, flags=flags)
+        torch.cuda.synchronize()
+        # resident: events around 10 activations; with transfers: host X in, host Y out, as the paper timed it
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            net.activate(X, V=V, Y=Y, flags=flags)
+        e1.record()
+        torch.cuda.synchronize()
+        gpu_us = e0.elapsed_time(e1) * 1e3 / 10
+        t0 = time.perf_counter()
+        for _ in range(10):
+            Xd = torch.from_numpy(wl.X).cuda()
+            net.activate(Xd, V=V, Y=Y, flags=flags)
+            y_host = Y.cpu()
+        copy_us = (time.perf_counter() - t0) * 1e6 / 10
+        oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.X)
+        cpu_us = 0.0
+        for _ in range(5):          # the node loop only: the paper times activation after its preprocessing
+            tm = {}
+            ref = oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.X, timing=tm)
+            cpu_us += tm["activation_seconds"] * 1e6 / 5
+        err = float(np.abs(net.values_original_order(V).cpu().numpy().astype(np.float64) - ref).max())
+        print(json.dumps({"regime": "paper: batch 1", "connections": wl.n_edges, "nodes": wl.n_nodes,
+                          "levels": net.n_levels,
+                          "schedule_taken": amd.asnn_activate_schedule(net.graph, 1, True, flags),
+                          "gpu_us_resident": round(gpu_us, 1),
+                          "gpu_us_with_host_copies": round(copy_us, 1), "cpu_oracle_us": round(cpu_us, 1),
+                          "speedup_resident": round(cpu_us / gpu_us, 2),
+                          "speedup_with_host_copies": round(cpu_us / copy_us, 2), "max_abs_err": err}), flush=True)
 
 
 def main():

@@ -967,10 +967,9 @@ inline long long tiles_for_workgroup(int B) {
     return (vecs + lpg - 1) / lpg;
 }
 
-// Dynamic LDS a staged workgroup needs; the packed network is staged when this fits the budget.
-// The static arrays of the kernel take up to 32 KB beside it.
-constexpr size_t kStagedLdsBudget = 96 * 1024;          // needs the kernel attribute raised
-constexpr size_t kStagedLdsBudgetDefault = 32 * 1024;   // fits without
+// Dynamic LDS a staged workgroup needs; the packed network is staged when this fits what a
+// workgroup may take beside the static arrays of the kernel (partial sums: 16 x T accumulators).
+constexpr size_t kLdsDefaultPerWorkgroup = 64 * 1024;   // without raising the kernel attribute
 inline size_t staged_lds_bytes(int n_nodes, int64_t n_edges, int n_levels, int T) {
     return (((size_t)n_nodes * (size_t)T * 4 + 15) & ~(size_t)15) + 4 * ((size_t)n_nodes + 1) + 8 * (size_t)n_edges +
            4 * ((size_t)ASNN_CLASSES * (size_t)n_levels + 1);
@@ -983,13 +982,19 @@ int launch_workgroup(const LevelArgs &a, const WorkgroupArgs &g) {
     const size_t lds = staged_lds_bytes(g.n_nodes, g.n_edges, g.n_levels, LPG * VEC);
     static size_t budget = 0;       // dynamic LDS this instantiation may take
     if (budget == 0) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&workgroup_kernel<VEC, LPG, ACC, kUnroll, true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStagedLdsBudget) == hipSuccess) {
-            budget = kStagedLdsBudget;
-        } else {
-            (void)hipGetLastError();
-            budget = kStagedLdsBudgetDefault;
-        }
+        const size_t fixed = sizeof(ACC) * kMixedWaves * LPG * VEC + 256;       // static LDS of the kernel, rounded up
+        int dev = 0, optin = 0;
+        size_t most = kLdsDefaultPerWorkgroup;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&optin, hipDeviceAttributeSharedMemPerBlockOptin, dev) == hipSuccess &&
+            (size_t)optin > most)
+            most = (size_t)optin;
+        budget = kLdsDefaultPerWorkgroup - fixed;
+        if (most > kLdsDefaultPerWorkgroup &&
+            hipFuncSetAttribute(reinterpret_cast<const void *>(&workgroup_kernel<VEC, LPG, ACC, kUnroll, true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)(most - fixed)) == hipSuccess)
+            budget = most - fixed;
+        (void)hipGetLastError();
     }
     if (lds <= budget) {
         hipLaunchKernelGGL((workgroup_kernel<VEC, LPG, ACC, kUnroll, true>), dim3((unsigned)tiles), dim3(kMixedBlock), lds,
