@@ -267,6 +267,16 @@ def test_degenerate_networks(amd):
         net, V, Y = run_gpu(amd, wl, flags=sched)
         assert net.n_levels == 5
         assert np.abs(net.values_original_order(V).cpu().numpy() - want).max() <= TIGHT
+    # no sensor at all: every root gives 0.5; no output requested either
+    wl = Workload("nosensor", 6, np.array([0, 1, 2, 2, 3], np.int32), np.array([2, 2, 3, 4, 5], np.int32),
+                  np.array([1.5, -0.5, 2.0, -2.0, 0.25], np.float32), np.zeros(0, np.int32), np.zeros(0, np.int32),
+                  np.zeros((0, 3), np.float32))
+    want = oracle.activate(6, wl.src, wl.dst, wl.w, wl.input_ids, wl.X)
+    assert want.shape == (6, 3)
+    for sched in (0, LEVELS, DATAFLOW, WORKGROUP):
+        net, V, Y = run_gpu(amd, wl, flags=sched)
+        got = net.values_original_order(V).cpu().numpy()
+        assert np.abs(got - want).max() <= TIGHT and (got[:2] == 0.5).all()
 
 
 def test_error_codes_from_device_checks(amd):
