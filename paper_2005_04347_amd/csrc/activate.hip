@@ -970,6 +970,7 @@ inline long long tiles_for_workgroup(int B) {
 // Dynamic LDS a staged workgroup needs; the packed network is staged when this fits what a
 // workgroup may take beside the static arrays of the kernel (partial sums: 16 x T accumulators).
 constexpr size_t kLdsDefaultPerWorkgroup = 64 * 1024;   // without raising the kernel attribute
+constexpr int kMaxDevices = 64;
 inline size_t staged_lds_bytes(int n_nodes, int64_t n_edges, int n_levels, int T) {
     return (((size_t)n_nodes * (size_t)T * 4 + 15) & ~(size_t)15) + 4 * ((size_t)n_nodes + 1) + 8 * (size_t)n_edges +
            4 * ((size_t)ASNN_CLASSES * (size_t)n_levels + 1);
@@ -980,13 +981,17 @@ int launch_workgroup(const LevelArgs &a, const WorkgroupArgs &g) {
     const int vecs = a.B / VEC;
     const int tiles = (vecs + LPG - 1) / LPG;
     const size_t lds = staged_lds_bytes(g.n_nodes, g.n_edges, g.n_levels, LPG * VEC);
-    static size_t budget = 0;       // dynamic LDS this instantiation may take
+    // dynamic LDS this instantiation may take on the current device (the attribute is per device)
+    static size_t budgets[kMaxDevices] = {};
+    int dev = 0;
+    ASNN_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return ASNN_ERR_NO_DEVICE;
+    size_t &budget = budgets[dev];
     if (budget == 0) {
         const size_t fixed = sizeof(ACC) * kMixedWaves * LPG * VEC + 256;       // static LDS of the kernel, rounded up
-        int dev = 0, optin = 0;
+        int optin = 0;
         size_t most = kLdsDefaultPerWorkgroup;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&optin, hipDeviceAttributeSharedMemPerBlockOptin, dev) == hipSuccess &&
+        if (hipDeviceGetAttribute(&optin, hipDeviceAttributeSharedMemPerBlockOptin, dev) == hipSuccess &&
             (size_t)optin > most)
             most = (size_t)optin;
         budget = kLdsDefaultPerWorkgroup - fixed;
@@ -1197,13 +1202,15 @@ extern "C" int asnn_activate(const asnn_packed *packed, const int32_t *input_ids
         }
     }
     if (dataflow) {
-        static int cus = 0;
+        static int cus_of[kMaxDevices] = {};
+        int dev = 0;
+        ASNN_HIP_TRY(hipGetDevice(&dev));
+        if (dev < 0 || dev >= kMaxDevices) return ASNN_ERR_NO_DEVICE;
+        int &cus = cus_of[dev];
         if (cus == 0) {
-            int dev = 0;
-            hipDeviceProp_t prop;
-            ASNN_HIP_TRY(hipGetDevice(&dev));
-            ASNN_HIP_TRY(hipGetDeviceProperties(&prop, dev));
-            cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
+            int n = 0;
+            ASNN_HIP_TRY(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev));
+            cus = n > 0 ? n : 1;
         }
         ActivateWorkspace ws = carve_activate(workspace, packed, B);
         const size_t n_values = (size_t)(n_nodes - first_row) * (size_t)B;
