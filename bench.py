@@ -163,6 +163,21 @@ def main():
         torch.cuda.synchronize()
         step = graph.replay
 
+    # yardstick: what a plain streaming copy sustains on this device (read + write bytes)
+    n_copy = 256 * 1024 * 1024
+    ca = torch.empty(n_copy, dtype=torch.float32, device=dev)
+    cb = torch.empty(n_copy, dtype=torch.float32, device=dev)
+    for _ in range(2):
+        amd.asnn_device_copy(cb, ca)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        amd.asnn_device_copy(cb, ca)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 5 * 2.0 * 4.0 * n_copy / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del ca, cb
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -185,21 +200,6 @@ def main():
     net.check(B)                                    # raises if a dataflow wait gave up
     dev_ms = sorted(a.elapsed_time(b) for a, b in ev)
     dev_ms_med = dev_ms[len(dev_ms) // 2]
-
-    # yardstick: what a plain streaming copy sustains on this device (read + write bytes)
-    n_copy = 256 * 1024 * 1024
-    ca = torch.empty(n_copy, dtype=torch.float32, device=dev)
-    cb = torch.empty(n_copy, dtype=torch.float32, device=dev)
-    for _ in range(2):
-        amd.asnn_device_copy(cb, ca)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(5):
-        amd.asnn_device_copy(cb, ca)
-    e1.record()
-    torch.cuda.synchronize()
-    copy_gbps = 5 * 2.0 * 4.0 * n_copy / (e0.elapsed_time(e1) * 1e-3) / 1e9
-    del ca, cb
 
     edge_samples = float(wl.n_edges) * B
     value = edge_samples / (wall_ms * 1e-3) / 1e9
