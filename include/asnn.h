@@ -207,7 +207,9 @@ int asnn_pack_csr(const int32_t *src, const int32_t *dst, const float *w, const 
  *   workspace   device, >= asnn_activate_workspace_bytes(packed, B), 256-byte aligned,
  *               or NULL (no dataflow schedule then).  256 bytes, plus
  *               n_edges*B/32 bytes (B rounded up to whole tiles) when a node has more
- *               than 512 connections.  Contents need not be preserved.
+ *               than 512 connections.  Contents need not be preserved between calls;
+ *               activations that may overlap in time (different streams) need a
+ *               workspace each.
  * Ids outside [0,n_nodes) in input_ids / output_ids are skipped (an output row
  * of such an id is filled with NaN).  Errors: NULL, SIZE, WORKSPACE, HIP.
  * Asynchronous.  A dataflow wait that exceeds its time limit (it cannot with
