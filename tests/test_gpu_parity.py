@@ -521,3 +521,47 @@ def test_value_matrix_beyond_4_gib(amd):
         assert err <= TIGHT, (sched, err)
         assert not torch.isnan(V[-1]).any() and not torch.isnan(V[wl.n_nodes // 2]).any()
         del V, Y
+
+
+def _random_network(seed):
+    """Random DAG with parallel connections, roots that are no sensors, a few very heavy nodes
+    (in-degrees around the chunking limits of the dataflow schedule) and several components."""
+    from workloads import Workload
+    rng = np.random.default_rng(1000 + seed)
+    n = int(rng.integers(2, 400))
+    order = rng.permutation(n)                         # order[k] = id of the k-th node in topological order
+    n_edges = int(rng.integers(0, 6 * n))
+    a = rng.integers(0, n - 1, size=n_edges)
+    b = rng.integers(0, n, size=n_edges)
+    lo, hi = np.minimum(a, b), np.maximum(a, b)
+    keep = lo < hi
+    src, dst = list(order[lo[keep]]), list(order[hi[keep]])
+    for d in rng.choice([40, 255, 256, 300, 511, 512, 513, 1024, 1025, 8192, 8193, 9000], size=int(rng.integers(0, 4))):
+        k = int(rng.integers(1, n))                    # position of the heavy node; its sources come before it
+        src += list(order[rng.integers(0, k, size=int(d))])
+        dst += [order[k]] * int(d)
+    src = np.array(src, dtype=np.int32); dst = np.array(dst, dtype=np.int32)
+    w = rng.uniform(-1.5, 1.5, size=src.shape[0]).astype(np.float32)
+    indeg = np.bincount(dst, minlength=n)
+    roots = np.nonzero(indeg == 0)[0]
+    inputs = rng.permutation(roots)[: max(1, len(roots) * 2 // 3)].astype(np.int32)      # the other roots stay at 0.5
+    outputs = rng.permutation(n)[: int(rng.integers(1, n + 1))].astype(np.int32)
+    B = int(rng.choice([1, 2, 3, 5, 8, 16, 33, 64, 65, 128, 200, 256, 300]))
+    X = rng.uniform(-1, 2, size=(len(inputs), B)).astype(np.float32)
+    return Workload(f"random{seed}", n, src, dst, w, inputs, outputs, X)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_networks_every_schedule_and_mode(amd, seed):
+    wl = _random_network(seed)
+    lv_o, nl_o = oracle.levels(wl.n_nodes, wl.src, wl.dst)
+    want = oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.X)
+    net = amd.Network(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.output_ids)
+    assert net.n_levels == nl_o and (net.level.cpu().numpy() == lv_o).all()
+    for sched in (0, LEVELS, DATAFLOW, WORKGROUP):
+        for fast, bound in ((0, TIGHT), (amd.FLAG_ACC_F32, 30 * TOL)):
+            _, V, Y = run_gpu(amd, wl, flags=sched | fast, net=net)
+            got = net.values_original_order(V).cpu().numpy()
+            err = float(np.abs(got.astype(np.float64) - want).max())
+            assert err <= bound, (seed, sched, fast, wl.n_nodes, wl.n_edges, wl.B, err)
+            assert (Y.cpu().numpy() == got[wl.output_ids]).all()
