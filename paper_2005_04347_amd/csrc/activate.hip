@@ -9,7 +9,7 @@
 // fetched once per wave through the scalar path and reused across the whole
 // tile).  For narrow batches the 64 lanes split into G groups that walk G
 // connections at a time and are folded with a fixed butterfly.  Rows with many
-// connections are shared by 4 (medium) or 16 (heavy) wavefronts whose partial
+// connections are shared by 8 (medium) or 16 (heavy) wavefronts whose partial
 // sums meet in LDS in wave order.  Nothing depends on timing: the same inputs
 // give the same bits.  The layer barrier is the boundary between two launches
 // on the stream; a second schedule (further down) replaces the barriers by
@@ -26,7 +26,7 @@ namespace {
 
 constexpr int kMixedBlock = 1024;                    // 16 wavefronts
 constexpr int kMixedWaves = kMixedBlock / kWave;
-constexpr int kMediumWaves = 4;                      // wavefronts per medium row
+constexpr int kMediumWaves = 8;                      // wavefronts per medium row in a level launch
 constexpr int kUnroll = 8;                           // row tiles in flight per wavefront
 
 template <int VEC> struct Vec;
@@ -172,7 +172,7 @@ __global__ __launch_bounds__(kWave) void gather_light_kernel(const int32_t *__re
 
 // A level that holds heavy or medium rows: one launch of 16-wave blocks.
 // Blocks [0, heavy_items) take one heavy (row, tile) each, all 16 waves on it;
-// the next medium_blocks blocks take four medium (row, tile) items, 4 waves on
+// the next medium_blocks blocks take two medium (row, tile) items, 8 waves on
 // each; the remaining blocks take sixteen light items, one wave each.  The
 // waves of one item split its connections into contiguous chunks; partial sums
 // meet in LDS and are added in wave order.
