@@ -11,9 +11,15 @@
 // connections at a time and are folded with a fixed butterfly.  Rows with many
 // connections are shared by 8 (medium) or 16 (heavy) wavefronts whose partial
 // sums meet in LDS in wave order.  Nothing depends on timing: the same inputs
-// give the same bits.  The layer barrier is the boundary between two launches
-// on the stream; a second schedule (further down) replaces the barriers by
-// per-row waiting inside one persistent launch.
+// give the same bits.
+//
+// Three schedules provide the layer barrier (all produce identical values):
+//   level launches  the boundary between two launches on the stream;
+//   dataflow        one persistent launch in which a row waits only for its own
+//                   source rows (for deep networks with small layers);
+//   workgroup       the paper's arrangement, one workgroup per tile of batch
+//                   columns walking all layers behind a workgroup barrier, in
+//                   one launch (for small networks and narrow batches).
 //
 // Arithmetic: products and sums in ACC (double by default, float with
 // ASNN_FLAG_ACC_F32), sigmoid(x) = 1/(1+e^(-4.97x)) in ACC, one rounding to
