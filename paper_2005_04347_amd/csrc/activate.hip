@@ -303,7 +303,9 @@ __device__ inline bool shows_not_ready(const float (&v)[VEC]) {
 }
 
 // Partial sums of the chunks of a split heavy row travel through the workspace in ACC precision,
-// marked "not written yet" the same way (for double: the pattern in the high word, zero below).
+// marked "not written yet" the same way.  For double the pattern sits in the high word, where it
+// reads as a number near 7e306: no sum of products of floats comes anywhere near (at most
+// 2^128 * 2^128 per product), so it cannot be taken for a value either.
 template <typename ACC> struct PartialBits;
 template <> struct PartialBits<float> {
     __device__ static inline float load(__amdgpu_buffer_rsrc_t r, uint32_t off, bool &ready) {
