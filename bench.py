@@ -34,6 +34,16 @@ def algorithmic_bytes(n_nodes, n_edges, n_inputs, B):
     return gather + store + csr + inputs
 
 
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown CPU"
+
+
 def measured_traffic(config, flags):
     """HBM bytes per level launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary of this
     workload (counter runs cannot be made from inside this process); None when no summary covers it."""
@@ -266,7 +276,7 @@ def main():
             "value": round(float(wl.n_edges) * cols / cpu_s / 1e9, 4), "unit": "G edge*samples/s", "cores": 1,
             "kind": "oracle",
             "sample": f"the same network, first {cols} of {B} batch columns (columns are independent), "
-                      f"{cpu_s:.2f} s single-threaded on {os.cpu_count()} visible host cores",
+                      f"{cpu_s:.2f} s single-threaded on {os.cpu_count()} visible host cores ({cpu_model()})",
         }
     print(json.dumps(out))
 
