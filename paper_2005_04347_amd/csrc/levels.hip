@@ -17,6 +17,7 @@ constexpr int kThreads = 256;
 constexpr int kSweepsPerSync = 64;     // frontier sweeps enqueued between two host reads
 constexpr int kGroup = 16;             // lanes that share one frontier node's out-edges
 constexpr unsigned kSweepBlocks = 512;
+constexpr int kFoundCap = 2048;            // frontier nodes a workgroup collects in LDS before appending them
 constexpr int kAggregateIndegree = 1024;   // networks with a node this heavy aggregate their releases per workgroup
 
 // Slots of the small control block in device memory.
@@ -83,17 +84,36 @@ __global__ void fill_out_kernel(const int32_t *__restrict__ src, const int32_t *
     }
 }
 
-__global__ void first_frontier_kernel(int32_t n_nodes, const int32_t *__restrict__ indeg, int32_t *__restrict__ level,
-                                      int32_t *__restrict__ frontier, int *ctl) {
-    const int v = blockIdx.x * blockDim.x + threadIdx.x;
-    const int32_t d = v < n_nodes ? indeg[v] : 0;
-    const bool root = v < n_nodes && d == 0;
-    if (v < n_nodes) level[v] = root ? 0 : -1;
-    wave_append(root, v, frontier, &ctl[kCount0]);
-    int32_t m = d;                                   // largest in-degree: one atomic per wavefront that can raise it
+// Level 0 = every node without an incoming connection; also finds the largest in-degree.
+// Grid-stride over the nodes; a workgroup collects its roots in LDS and appends them with one
+// atomic on the frontier size (see sweep_kernel).
+__global__ __launch_bounds__(kThreads) void first_frontier_kernel(int32_t n_nodes, const int32_t *__restrict__ indeg,
+                                                                   int32_t *__restrict__ level,
+                                                                   int32_t *__restrict__ frontier, int *ctl) {
+    __shared__ int32_t found[kFoundCap];
+    __shared__ int n_found, found_base;
+    if (threadIdx.x == 0) n_found = 0;
+    __syncthreads();
+    int32_t m = 0;
+    const int stride = gridDim.x * kThreads;
+    for (int v = blockIdx.x * kThreads + threadIdx.x; v < n_nodes; v += stride) {
+        const int32_t d = indeg[v];
+        m = max(m, d);
+        level[v] = d == 0 ? 0 : -1;
+        if (d == 0) {
+            const int pos = atomicAdd(&n_found, 1);                      // LDS
+            if (pos < kFoundCap) found[pos] = v;
+            else frontier[atomicAdd(&ctl[kCount0], 1)] = v;              // LDS list full: append directly
+        }
+    }
 #pragma unroll
     for (int off = 1; off < kWave; off <<= 1) m = max(m, __shfl_xor(m, off, kWave));
     if ((threadIdx.x & (kWave - 1)) == 0 && m >= kAggregateIndegree) atomicMax(&ctl[kMaxIndeg], m);
+    __syncthreads();
+    const int n = min(n_found, kFoundCap);
+    if (threadIdx.x == 0 && n > 0) found_base = atomicAdd(&ctl[kCount0], n);
+    __syncthreads();
+    for (int i = threadIdx.x; i < n; i += kThreads) frontier[found_base + i] = found[i];
 }
 
 // One sweep: every node of frontier k releases its out-edges; a destination
@@ -112,7 +132,6 @@ __global__ void first_frontier_kernel(int32_t n_nodes, const int32_t *__restrict
 // it.  The path costs three workgroup barriers per round, so networks without
 // heavy nodes (every wavefront on its own, no barrier) do not take it.
 constexpr int kSweepSlots = 2 * kThreads;      // hash slots per workgroup: at most kThreads insertions per round
-constexpr int kFoundCap = 2048;                // next-frontier nodes a workgroup collects in LDS before appending
 
 __global__ __launch_bounds__(kThreads) void sweep_kernel(int k, const int32_t *__restrict__ out_ptr,
                                                           const int32_t *__restrict__ out_dst, int32_t *indeg,
@@ -279,7 +298,7 @@ extern "C" int asnn_build_levels(int32_t n_nodes, int64_t n_edges, const int32_t
                            src, dst, n_edges, n_nodes, (const int32_t *)w.out_ptr, w.cursor, w.out_dst);
         ASNN_HIP_TRY(hipGetLastError());
     }
-    hipLaunchKernelGGL(first_frontier_kernel, dim3(blocks_for((size_t)n_nodes, kThreads)), dim3(kThreads), 0, s,
+    hipLaunchKernelGGL(first_frontier_kernel, dim3(blocks_for((size_t)n_nodes, 4 * kThreads, 2048)), dim3(kThreads), 0, s,
                        n_nodes, (const int32_t *)w.indeg, level_out, w.frontier_a, w.ctl);
     ASNN_HIP_TRY(hipGetLastError());
 
