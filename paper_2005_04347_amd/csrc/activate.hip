@@ -468,7 +468,10 @@ __global__ __launch_bounds__(kMixedBlock) void dataflow_kernel(const int32_t *__
                                                                 int first_unit, int n_work, int tiles, int first_row,
                                                                 DataflowCtl *ctl, void *partials, uint32_t partial_bytes) {
     constexpr int T = LPG * VEC;
-    __shared__ ACC part[kMixedWaves][LPG * VEC];
+    constexpr int E = T >= kWave ? T / kWave : 1;       // tile elements per lane when one wavefront holds the tile
+    constexpr int EL = T >= kWave ? kWave : T;          // lanes that hold them
+    __shared__ ACC part[kMixedWaves][T];
+    __shared__ ACC others[kMaxHeavyChunks - 1][T];      // partial sums of the other chunks of a split row
     __shared__ int s_claim;
     const __amdgpu_buffer_rsrc_t vres = __builtin_amdgcn_make_buffer_rsrc(V, 0, (int)v_bytes, kBufferFlags);
     const __amdgpu_buffer_rsrc_t pres = __builtin_amdgcn_make_buffer_rsrc(partials, 0, (int)partial_bytes, kBufferFlags);
@@ -516,64 +519,72 @@ __global__ __launch_bounds__(kMixedBlock) void dataflow_kernel(const int32_t *__
 #pragma unroll
             for (int j = 0; j < VEC; ++j) acc[j] = ACC(0);
         }
-        if (share > 1) {                               // block-uniform
+        if (share > 1) {                               // block-uniform: a heavy or medium row, `row` is r0
+            // The wavefronts' partial sums meet in LDS.  From here on the tile is spread over all
+            // lanes of wavefront 0 (E elements per lane), so that the additions, the sigmoid and the
+            // store that follow the last gathered source take as few instructions as possible.
             if (lane < LPG) {
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) part[wave][lane * VEC + j] = acc[j];
             }
-            __syncthreads();
-            if (slice == 0 && lane < LPG) {
-#pragma unroll
-                for (int j = 0; j < VEC; ++j) {
-                    ACC s = ACC(0);
-                    for (int k = 0; k < share; ++k) s += part[wave + k][lane * VEC + j];
-                    acc[j] = s;
-                }
-            }
-        }
-        if (n_chunks > 1 && wave == 0) {               // wave-uniform
-            // element (slot, tile, column) of the partial-sum area, in bytes
+            const bool split = n_chunks > 1, last_chunk = chunk == n_chunks - 1;     // block-uniform
             const uint32_t slot0 = partial_slot(row0_begin);
-            const uint32_t in_slot = (uint32_t)tile * T + (uint32_t)(lane % LPG) * VEC;
             const uint32_t slot_elems = (uint32_t)tiles * T;
-            if (chunk < n_chunks - 1) {
-                // not the last chunk: hand the partial sum to the unit that holds the last one
-                if (lane < LPG) {
-#pragma unroll
-                    for (int j = 0; j < VEC; ++j)
-                        PartialBits<ACC>::store(pres, (uint32_t)(((slot0 + chunk) * slot_elems + in_slot + j) * sizeof(ACC)), acc[j]);
-                }
-            } else {
-                // the last chunk adds the others in chunk order, then its own
-                ACC total[VEC];
-#pragma unroll
-                for (int j = 0; j < VEC; ++j) total[j] = ACC(0);
+            const uint32_t el = (uint32_t)lane * E;            // this lane's first element of the tile
+            if (split && last_chunk && wave < n_chunks - 1 && lane < EL) {
+                // The unit that holds the last chunk of a split row collects the partial sums of the
+                // other chunks: wavefront k waits for chunk k, so the waits overlap.
+                ACC p[E];
                 Patience patience;
-                for (int k = 0; k < n_chunks - 1; ++k) {
-                    ACC p[VEC];
-                    for (;;) {
-                        bool ok = true;
-                        if (lane < LPG) {
+                for (;;) {
+                    bool ok = true;
 #pragma unroll
-                            for (int j = 0; j < VEC; ++j) {
-                                bool ready;
-                                p[j] = PartialBits<ACC>::load(pres, (uint32_t)(((slot0 + k) * slot_elems + in_slot + j) * sizeof(ACC)), ready);
-                                ok = ok && ready;
-                            }
-                        } else {
-#pragma unroll
-                            for (int j = 0; j < VEC; ++j) p[j] = ACC(0);
-                        }
-                        if (__all(ok) || !patience.again(ctl)) break;
+                    for (int j = 0; j < E; ++j) {
+                        bool ready;
+                        p[j] = PartialBits<ACC>::load(pres, (uint32_t)(((slot0 + wave) * slot_elems + (uint32_t)tile * T + el + j) * sizeof(ACC)), ready);
+                        ok = ok && ready;
                     }
-#pragma unroll
-                    for (int j = 0; j < VEC; ++j) total[j] += p[j];
+                    if (ok || !patience.again(ctl)) break;
                 }
 #pragma unroll
-                for (int j = 0; j < VEC; ++j) acc[j] = total[j] + acc[j];
+                for (int j = 0; j < E; ++j) others[wave][el + j] = p[j];
             }
-        }
-        if (active && slice == 0 && lane < LPG && chunk == n_chunks - 1) {
+            __syncthreads();
+            if (wave == 0 && lane < EL) {
+                ACC sum[E];
+#pragma unroll
+                for (int j = 0; j < E; ++j) {
+                    ACC t = ACC(0);
+#pragma unroll
+                    for (int k = 0; k < kMixedWaves; ++k) t += part[k][el + j];
+                    sum[j] = t;
+                }
+                if (split && !last_chunk) {
+                    // not the last chunk: hand the partial sum to the unit that holds the last one
+#pragma unroll
+                    for (int j = 0; j < E; ++j)
+                        PartialBits<ACC>::store(pres, (uint32_t)(((slot0 + chunk) * slot_elems + (uint32_t)tile * T + el + j) * sizeof(ACC)), sum[j]);
+                } else {
+                    if (split) {
+                        // the last chunk adds the others in chunk order, then its own
+#pragma unroll
+                        for (int j = 0; j < E; ++j) {
+                            ACC total = ACC(0);
+#pragma unroll 1
+                            for (int k = 0; k < n_chunks - 1; ++k) total += others[k][el + j];
+                            sum[j] = total + sum[j];
+                        }
+                    }
+                    const uint32_t ce = (uint32_t)tile * T + el;
+                    if (ce < (uint32_t)B) {
+                        float out[E];
+#pragma unroll
+                        for (int j = 0; j < E; ++j) out[j] = squash(sum[j]);
+                        store_vec_device_scope<E>(vres, ((uint32_t)row * (uint32_t)B + ce) * 4u, out);
+                    }
+                }
+            }
+        } else if (active && lane < LPG) {               // light rows: one wavefront each
             float out[VEC];
 #pragma unroll
             for (int j = 0; j < VEC; ++j) out[j] = squash(acc[j]);
