@@ -17,15 +17,27 @@ constexpr int kThreads = 256;
 constexpr int kSweepsPerSync = 64;     // frontier sweeps enqueued between two host reads
 constexpr int kGroup = 16;             // lanes that share one frontier node's out-edges
 constexpr unsigned kSweepBlocks = 512;
-constexpr int kFoundCap = 2048;            // frontier nodes a workgroup collects in LDS before appending them
-constexpr int kAggregateIndegree = 1024;   // networks with a node this heavy aggregate their releases per workgroup
+constexpr int kFoundCap = 2048;        // frontier nodes a workgroup collects in LDS before appending them
+// A destination with this many incoming connections can receive thousands of returning atomics
+// on its counter in one sweep, which serialise.  Its entries in the out-adjacency carry kHotBit, and
+// a workgroup first adds up its releases of such destinations in a small LDS hash table.
+constexpr int kHotIndegree = ASNN_HEAVY_INDEGREE;
+constexpr int32_t kHotBit = INT32_MIN;
+constexpr int kHotSlots = 1024;        // hash slots per workgroup
+constexpr int kHotProbes = 16;         // after that many occupied slots the release goes straight to memory
+// Narrow frontiers: one workgroup runs sweep after sweep without leaving the device.
+constexpr int kNarrowThreads = 1024;
+constexpr int kNarrowCap = 2048;       // frontier nodes it keeps in LDS
+constexpr int kNarrowMaxEdges = 4096;  // out-edges of one frontier it still takes alone (a single compute unit issues about one request per clock)
+constexpr int kNarrowBatch = 16;       // out-edges a thread releases per round trip
+constexpr int kNarrowBigOut = 64;      // out-degree from which the whole workgroup shares a node
 
 // Slots of the small control block in device memory.
 enum Ctl : int {
     kErr = 0,          // first error code seen (0 = none)
     kAssigned = 1,     // nodes that received a level so far
     kLevels = 2,       // number of non-empty frontiers so far
-    kMaxIndeg = 3,     // largest in-degree of the network
+    kSweep = 3,        // index of the next sweep (written by narrow_sweeps_kernel)
     kCount0 = 4,       // three rotating frontier sizes: sweep k reads kCount0 + k % 3
     kCtlInts = 16
 };
@@ -71,20 +83,22 @@ __global__ void mark_inputs_kernel(const int32_t *__restrict__ input_ids, int32_
     if (indeg[v] != 0) flag_error(ctl, ASNN_ERR_INPUT_HAS_INEDGE);
 }
 
-// out_dst grouped by source; the order inside a group is irrelevant for levels.
+// out_dst grouped by source; the order inside a group is irrelevant for levels.  With indeg given
+// (the final in-degrees: the sweeps have not started), destinations with many incoming
+// connections are marked with kHotBit.
 __global__ void fill_out_kernel(const int32_t *__restrict__ src, const int32_t *__restrict__ dst, int64_t n_edges,
                                 int32_t n_nodes, const int32_t *__restrict__ out_ptr, int32_t *cursor,
-                                int32_t *__restrict__ out_dst) {
+                                const int32_t *__restrict__ indeg, int32_t *__restrict__ out_dst) {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n_edges; e += stride) {
         const int32_t a = src[e], b = dst[e];
         if (a < 0 || a >= n_nodes || b < 0 || b >= n_nodes) continue;   // already flagged
         const int32_t pos = out_ptr[a] + atomicAdd(&cursor[a], 1);
-        out_dst[pos] = b;
+        out_dst[pos] = (indeg != nullptr && indeg[b] >= kHotIndegree) ? (b | kHotBit) : b;
     }
 }
 
-// Level 0 = every node without an incoming connection; also finds the largest in-degree.
+// Level 0 = every node without an incoming connection.
 // Grid-stride over the nodes; a workgroup collects its roots in LDS and appends them with one
 // atomic on the frontier size (see sweep_kernel).
 __global__ __launch_bounds__(kThreads) void first_frontier_kernel(int32_t n_nodes, const int32_t *__restrict__ indeg,
@@ -94,11 +108,9 @@ __global__ __launch_bounds__(kThreads) void first_frontier_kernel(int32_t n_node
     __shared__ int n_found, found_base;
     if (threadIdx.x == 0) n_found = 0;
     __syncthreads();
-    int32_t m = 0;
     const int stride = gridDim.x * kThreads;
     for (int v = blockIdx.x * kThreads + threadIdx.x; v < n_nodes; v += stride) {
         const int32_t d = indeg[v];
-        m = max(m, d);
         level[v] = d == 0 ? 0 : -1;
         if (d == 0) {
             const int pos = atomicAdd(&n_found, 1);                      // LDS
@@ -106,9 +118,6 @@ __global__ __launch_bounds__(kThreads) void first_frontier_kernel(int32_t n_node
             else frontier[atomicAdd(&ctl[kCount0], 1)] = v;              // LDS list full: append directly
         }
     }
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) m = max(m, __shfl_xor(m, off, kWave));
-    if ((threadIdx.x & (kWave - 1)) == 0 && m >= kAggregateIndegree) atomicMax(&ctl[kMaxIndeg], m);
     __syncthreads();
     const int n = min(n_found, kFoundCap);
     if (threadIdx.x == 0 && n > 0) found_base = atomicAdd(&ctl[kCount0], n);
@@ -116,31 +125,43 @@ __global__ __launch_bounds__(kThreads) void first_frontier_kernel(int32_t n_node
     for (int i = threadIdx.x; i < n; i += kThreads) frontier[found_base + i] = found[i];
 }
 
+// Adds one release of hot destination u to the workgroup's hash table (slot_node preset to -1,
+// slot_count to 0).  Returns false when kHotProbes slots in a row belong to other nodes: the
+// caller then releases u in memory like any other destination.
+__device__ inline bool hot_add(int32_t u, int32_t *slot_node, int32_t *slot_count) {
+    unsigned h = ((unsigned)u * 2654435761u) >> 12;
+    for (int probe = 0; probe < kHotProbes; ++probe, ++h) {
+        h &= (unsigned)(kHotSlots - 1);
+        const int32_t seen = atomicCAS(&slot_node[h], -1, u);
+        if (seen == -1 || seen == u) {
+            atomicAdd(&slot_count[h], 1);
+            return true;
+        }
+    }
+    return false;
+}
+
 // One sweep: every node of frontier k releases its out-edges; a destination
 // whose remaining in-degree drops to zero gets level k+1 and joins frontier k+1.
 // A sweep over an empty frontier does nothing, so the host may enqueue more
 // sweeps than the network has layers.
 //
-// 16 lanes share one frontier node's out-edges.  When the network holds a node
-// with thousands of incoming connections, that node receives thousands of
-// returning atomics on one address per sweep, which serialise (on a 1000-layer
-// network whose layers each hold such a node that was more than half of the
-// sweep time).  Such networks take the aggregating path: a workgroup handles
-// 16 frontier nodes at a time and first adds up its releases per destination
-// in a small LDS hash table, so a destination is decremented once per
-// workgroup and round, by the number of connections the workgroup's nodes send
-// it.  The path costs three workgroup barriers per round, so networks without
-// heavy nodes (every wavefront on its own, no barrier) do not take it.
-constexpr int kSweepSlots = 2 * kThreads;      // hash slots per workgroup: at most kThreads insertions per round
-
+// 16 lanes share one frontier node's out-edges.  The nodes a workgroup adds to
+// the next frontier are collected in LDS and appended with ONE atomic on the
+// frontier size (with tens of thousands of nodes per frontier, one atomic per
+// wavefront on that single address was most of the sweep time).  Releases of
+// hot destinations are first added up per workgroup in LDS, so such a
+// destination is decremented once per workgroup, by the number of connections
+// the workgroup's nodes send it.
 __global__ __launch_bounds__(kThreads) void sweep_kernel(int k, const int32_t *__restrict__ out_ptr,
                                                           const int32_t *__restrict__ out_dst, int32_t *indeg,
                                                           int32_t *__restrict__ level,
                                                           const int32_t *__restrict__ frontier_in,
                                                           int32_t *__restrict__ frontier_out, int *ctl) {
-    __shared__ int32_t slot_node[kSweepSlots];
-    __shared__ int32_t slot_count[kSweepSlots];
-    __shared__ int32_t s_rounds;
+    __shared__ int32_t slot_node[kHotSlots];
+    __shared__ int32_t slot_count[kHotSlots];
+    __shared__ int32_t found[kFoundCap];
+    __shared__ int n_found, found_base, n_hot;
     const int count = ctl[kCount0 + k % 3];
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         ctl[kCount0 + (k + 2) % 3] = 0;          // read by sweep k-1 (finished), filled by sweep k+1
@@ -154,75 +175,185 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(int k, const int32_t *_
     constexpr int kNodesPerBlock = kThreads / kGroup;
     const int sub = threadIdx.x % kGroup;
     const int stride = gridDim.x * kNodesPerBlock;
-    if (ctl[kMaxIndeg] < kAggregateIndegree) {       // grid-uniform
-        // The nodes this workgroup adds to the next frontier are collected in LDS and appended
-        // with ONE atomic on the frontier size: with tens of thousands of nodes per frontier,
-        // one atomic per wavefront on that single address was most of the sweep time.
-        __shared__ int32_t found[kFoundCap];
-        __shared__ int n_found, found_base;
-        if (threadIdx.x == 0) n_found = 0;
-        __syncthreads();
-        for (int f = blockIdx.x * kNodesPerBlock + threadIdx.x / kGroup; f < count; f += stride) {
-            const int32_t v = frontier_in[f];
-            const int32_t e1 = out_ptr[v + 1];
-            for (int32_t e = out_ptr[v] + sub; e < e1; e += kGroup) {
-                const int32_t u = out_dst[e];
-                const bool last = atomicSub(&indeg[u], 1) == 1;
-                if (last) {
-                    level[u] = k + 1;
-                    const int pos = atomicAdd(&n_found, 1);                  // LDS
-                    if (pos < kFoundCap) found[pos] = u;
-                    else frontier_out[atomicAdd(count_out, 1)] = u;          // LDS list full: append directly
-                }
+    if (threadIdx.x == 0) { n_found = 0; n_hot = 0; }
+    for (int i = threadIdx.x; i < kHotSlots; i += kThreads) { slot_node[i] = -1; slot_count[i] = 0; }
+    __syncthreads();
+    auto assign = [&](int32_t u) {
+        level[u] = k + 1;
+        const int pos = atomicAdd(&n_found, 1);                  // LDS
+        if (pos < kFoundCap) found[pos] = u;
+        else frontier_out[atomicAdd(count_out, 1)] = u;          // LDS list full: append directly
+    };
+    for (int f = blockIdx.x * kNodesPerBlock + threadIdx.x / kGroup; f < count; f += stride) {
+        const int32_t v = frontier_in[f];
+        const int32_t e1 = out_ptr[v + 1];
+        for (int32_t e = out_ptr[v] + sub; e < e1; e += kGroup) {
+            const int32_t raw = out_dst[e];
+            const int32_t u = raw & ~kHotBit;
+            if (raw < 0 && hot_add(u, slot_node, slot_count)) {
+                n_hot = 1;                                       // LDS, same value from every writer
+                continue;
+            }
+            if (atomicSub(&indeg[u], 1) == 1) assign(u);
+        }
+    }
+    __syncthreads();
+    if (n_hot != 0) {                                            // block-uniform
+        for (int i = threadIdx.x; i < kHotSlots; i += kThreads) {
+            const int32_t u = slot_node[i];
+            if (u >= 0) {
+                const int32_t c = slot_count[i];
+                if (atomicSub(&indeg[u], c) == c) assign(u);
             }
         }
         __syncthreads();
-        const int n = min(n_found, kFoundCap);
-        if (threadIdx.x == 0 && n > 0) found_base = atomicAdd(count_out, n);
-        __syncthreads();
-        for (int i = threadIdx.x; i < n; i += kThreads) frontier_out[found_base + i] = found[i];
+    }
+    const int n = min(n_found, kFoundCap);
+    if (threadIdx.x == 0 && n > 0) found_base = atomicAdd(count_out, n);
+    __syncthreads();
+    for (int i = threadIdx.x; i < n; i += kThreads) frontier_out[found_base + i] = found[i];
+}
+
+// Narrow frontiers.  A network with many small layers spends its sweeps on launches and on the
+// chain of device round trips inside each (frontier size, node, out-range, destination,
+// counter).  ONE workgroup therefore runs sweep after sweep, starting with sweep k0, for as long as
+// the frontier fits its LDS (kNarrowCap nodes, kNarrowMaxEdges out-edges): the frontier never leaves
+// LDS, the layer barrier is a workgroup barrier, and a thread releases up to kNarrowBatch out-edges
+// of its node per round trip.  It stops at the first frontier that is empty (the network is done) or
+// too wide; that frontier is then in frontier_a/frontier_b (by the parity of its sweep index) with
+// its size in the control block, and ctl[kSweep] names the sweep that comes next, exactly as
+// sweep_kernel expects it.
+__global__ __launch_bounds__(kNarrowThreads) void narrow_sweeps_kernel(int k0, const int32_t *__restrict__ out_ptr,
+                                                                       const int32_t *__restrict__ out_dst,
+                                                                       int32_t *indeg, int32_t *__restrict__ level,
+                                                                       int32_t *frontier_a, int32_t *frontier_b,
+                                                                       int *ctl) {
+    __shared__ int32_t fr[2][kNarrowCap];            // current and next frontier
+    __shared__ int32_t e_begin[kNarrowCap], e_end[kNarrowCap];
+    __shared__ int32_t big[kNarrowCap];              // positions of frontier nodes with many out-edges
+    __shared__ int32_t slot_node[kHotSlots];
+    __shared__ int32_t slot_count[kHotSlots];
+    __shared__ int n_next, n_big, n_edges_out, n_hot;
+    const int tid = threadIdx.x;
+    int k = k0;
+    int n_cur = ctl[kCount0 + k % 3];
+    if (n_cur <= 0 || n_cur > kNarrowCap) {          // block-uniform: nothing for this kernel to do
+        if (tid == 0) ctl[kSweep] = k;
         return;
     }
-    for (int base = blockIdx.x * kNodesPerBlock; base < count; base += stride) {      // block-uniform
-        const int f = base + threadIdx.x / kGroup;
-        int32_t e0 = 0, e1 = 0;
-        if (f < count) {
-            const int32_t v = frontier_in[f];
-            e0 = out_ptr[v];
-            e1 = out_ptr[v + 1];
+    {
+        const int32_t *f0 = (k & 1) ? frontier_b : frontier_a;
+        for (int i = tid; i < n_cur; i += kNarrowThreads) fr[0][i] = f0[i];
+    }
+    int cur = 0;
+    int assigned = 0, levels = 0;                    // what thread 0 reports at the end
+    bool in_lds_only = false;                        // the current frontier is not in global memory
+    int n_exit;                                      // size of the frontier the next kernel starts with
+    for (;;) {
+        if (tid == 0) { n_next = 0; n_big = 0; n_edges_out = 0; n_hot = 0; }
+        for (int i = tid; i < kHotSlots; i += kNarrowThreads) { slot_node[i] = -1; slot_count[i] = 0; }
+        __syncthreads();
+        int mine = 0;
+        for (int i = tid; i < n_cur; i += kNarrowThreads) {
+            const int32_t v = fr[cur][i];
+            const int32_t b = out_ptr[v], e = out_ptr[v + 1];
+            e_begin[i] = b;
+            e_end[i] = e;
+            mine += e - b;
+            if (e - b > kNarrowBigOut) big[atomicAdd(&n_big, 1)] = i;
         }
-        if (threadIdx.x == 0) s_rounds = 0;
+        if (mine > 0) atomicAdd(&n_edges_out, min(mine, kNarrowMaxEdges + 1));      // the sum cannot overflow
         __syncthreads();
-        if (sub == 0 && e1 > e0) atomicMax(&s_rounds, (e1 - e0 + kGroup - 1) / kGroup);
-        __syncthreads();
-        const int rounds = s_rounds;             // block-uniform: rounds of one out-edge per lane
-        for (int r = 0; r < rounds; ++r) {
-            for (int i = threadIdx.x; i < kSweepSlots; i += kThreads) { slot_node[i] = -1; slot_count[i] = 0; }
-            __syncthreads();
-            const int32_t e = e0 + r * kGroup + sub;
-            if (e < e1) {
-                const int32_t u = out_dst[e];
-                unsigned h = ((unsigned)u * 2654435761u) >> 7;
-                for (;;) {                       // at most kThreads keys in 2*kThreads slots: a free slot exists
-                    h &= (unsigned)(kSweepSlots - 1);
-                    const int32_t seen = atomicCAS(&slot_node[h], -1, u);
-                    if (seen == -1 || seen == u) { atomicAdd(&slot_count[h], 1); break; }
-                    ++h;
+        if (n_edges_out > kNarrowMaxEdges) {         // block-uniform: too much work for one workgroup
+            n_exit = n_cur;
+            if (in_lds_only) {
+                int32_t *f = (k & 1) ? frontier_b : frontier_a;
+                for (int i = tid; i < n_cur; i += kNarrowThreads) f[i] = fr[cur][i];
+            }
+            break;
+        }
+        assigned += n_cur;
+        levels = k + 1;
+        int32_t *spill = ((k + 1) & 1) ? frontier_b : frontier_a;      // where frontier k+1 goes beyond the LDS list
+        int32_t *next = fr[cur ^ 1];
+        auto assign = [&](int32_t u) {
+            level[u] = k + 1;
+            const int pos = atomicAdd(&n_next, 1);               // LDS
+            if (pos < kNarrowCap) next[pos] = u;
+            else spill[pos] = u;                                 // positions are final: this kernel owns the whole frontier
+        };
+        auto release = [&](int32_t raw) {
+            const int32_t u = raw & ~kHotBit;
+            if (raw < 0 && hot_add(u, slot_node, slot_count)) {
+                n_hot = 1;
+                return;
+            }
+            if (atomicSub(&indeg[u], 1) == 1) assign(u);
+        };
+        // one thread per frontier node, kNarrowBatch out-edges per round trip
+        for (int i = tid; i < n_cur; i += kNarrowThreads) {
+            const int32_t b = e_begin[i], e = e_end[i];
+            if (e - b > kNarrowBigOut) continue;
+            for (int32_t x = b; x < e; x += kNarrowBatch) {
+                int32_t raw[kNarrowBatch], old[kNarrowBatch];
+#pragma unroll
+                for (int j = 0; j < kNarrowBatch; ++j) raw[j] = out_dst[min(x + j, e - 1)];
+#pragma unroll
+                for (int j = 0; j < kNarrowBatch; ++j) {
+                    old[j] = 0;
+                    if (x + j < e && raw[j] >= 0) old[j] = atomicSub(&indeg[raw[j]], 1);
+                }
+#pragma unroll
+                for (int j = 0; j < kNarrowBatch; ++j) {
+                    if (x + j >= e) continue;
+                    if (raw[j] >= 0) {
+                        if (old[j] == 1) assign(raw[j]);
+                    } else {
+                        release(raw[j]);
+                    }
                 }
             }
-            __syncthreads();
-            for (int i = threadIdx.x; i < kSweepSlots; i += kThreads) {     // every thread: the same trip count
+        }
+        // nodes with many out-edges: the whole workgroup strides over each one's list
+        const int nb = n_big;                        // block-uniform (written before the last barrier)
+        for (int q = 0; q < nb; ++q) {
+            const int i = big[q];
+            const int32_t e = e_end[i];
+            for (int32_t x = e_begin[i] + tid; x < e; x += kNarrowThreads) release(out_dst[x]);
+        }
+        __syncthreads();
+        if (n_hot != 0) {                            // block-uniform
+            for (int i = tid; i < kHotSlots; i += kNarrowThreads) {
                 const int32_t u = slot_node[i];
-                bool last = false;
                 if (u >= 0) {
                     const int32_t c = slot_count[i];
-                    last = atomicSub(&indeg[u], c) == c;
-                    if (last) level[u] = k + 1;
+                    if (atomicSub(&indeg[u], c) == c) assign(u);
                 }
-                wave_append(last, u, frontier_out, count_out);
             }
             __syncthreads();
         }
+        const int n = n_next;                        // block-uniform
+        ++k;
+        if (n == 0 || n > kNarrowCap) {
+            n_exit = n;
+            if (n > kNarrowCap)                      // the first kNarrowCap nodes join the rest in global memory
+                for (int i = tid; i < kNarrowCap; i += kNarrowThreads) spill[i] = next[i];
+            break;
+        }
+        cur ^= 1;
+        n_cur = n;
+        in_lds_only = true;
+        __syncthreads();                             // n_next is reset at the top of the loop
+    }
+    if (tid == 0) {
+        if (assigned > 0) {
+            atomicAdd(&ctl[kAssigned], assigned);
+            ctl[kLevels] = levels;
+        }
+        ctl[kSweep] = k;
+        ctl[kCount0 + k % 3] = n_exit;
+        ctl[kCount0 + (k + 1) % 3] = 0;
+        ctl[kCount0 + (k + 2) % 3] = 0;
     }
 }
 
@@ -295,28 +426,45 @@ extern "C" int asnn_build_levels(int32_t n_nodes, int64_t n_edges, const int32_t
     ASNN_TRY(exclusive_scan_i32(w.out_ptr, w.out_ptr, (size_t)n_nodes + 1, w.scan_tmp, s));
     if (n_edges > 0) {
         hipLaunchKernelGGL(fill_out_kernel, dim3(blocks_for((size_t)n_edges, kThreads, 65535)), dim3(kThreads), 0, s,
-                           src, dst, n_edges, n_nodes, (const int32_t *)w.out_ptr, w.cursor, w.out_dst);
+                           src, dst, n_edges, n_nodes, (const int32_t *)w.out_ptr, w.cursor, (const int32_t *)w.indeg,
+                           w.out_dst);
         ASNN_HIP_TRY(hipGetLastError());
     }
     hipLaunchKernelGGL(first_frontier_kernel, dim3(blocks_for((size_t)n_nodes, 4 * kThreads, 2048)), dim3(kThreads), 0, s,
                        n_nodes, (const int32_t *)w.indeg, level_out, w.frontier_a, w.ctl);
     ASNN_HIP_TRY(hipGetLastError());
 
+    // Grid-wide sweeps are enqueued kSweepsPerSync at a time between two looks at the control block.
+    // Where the frontier looks small enough for one workgroup (its size times the mean out-degree),
+    // narrow_sweeps_kernel takes over and runs sweep after sweep on the device until the frontier is
+    // empty or outgrows it.  The first frontier is not known to the host: small networks start narrow.
+    const int64_t mean_out = n_edges / n_nodes > 1 ? n_edges / n_nodes : 1;
+    bool narrow = n_edges <= 16LL * kNarrowMaxEdges;
     int host_ctl[kCtlInts];
     int k = 0;
     for (;;) {
-        for (int i = 0; i < kSweepsPerSync; ++i, ++k) {
-            const int32_t *fin = (k & 1) ? w.frontier_b : w.frontier_a;
-            int32_t *fout = (k & 1) ? w.frontier_a : w.frontier_b;
-            hipLaunchKernelGGL(sweep_kernel, dim3(kSweepBlocks), dim3(kThreads), 0, s, k, (const int32_t *)w.out_ptr,
-                               (const int32_t *)w.out_dst, w.indeg, level_out, fin, fout, w.ctl);
+        if (narrow) {
+            hipLaunchKernelGGL(narrow_sweeps_kernel, dim3(1), dim3(kNarrowThreads), 0, s, k, (const int32_t *)w.out_ptr,
+                               (const int32_t *)w.out_dst, w.indeg, level_out, w.frontier_a, w.frontier_b, w.ctl);
             ASNN_HIP_TRY(hipGetLastError());
+        } else {
+            for (int i = 0; i < kSweepsPerSync; ++i, ++k) {
+                const int32_t *fin = (k & 1) ? w.frontier_b : w.frontier_a;
+                int32_t *fout = (k & 1) ? w.frontier_a : w.frontier_b;
+                hipLaunchKernelGGL(sweep_kernel, dim3(kSweepBlocks), dim3(kThreads), 0, s, k, (const int32_t *)w.out_ptr,
+                                   (const int32_t *)w.out_dst, w.indeg, level_out, fin, fout, w.ctl);
+                ASNN_HIP_TRY(hipGetLastError());
+            }
         }
         ASNN_HIP_TRY(hipMemcpyAsync(host_ctl, w.ctl, sizeof(host_ctl), hipMemcpyDeviceToHost, s));
         ASNN_HIP_TRY(hipStreamSynchronize(s));
         if (host_ctl[kErr] != 0) return host_ctl[kErr];
-        if (host_ctl[kCount0 + k % 3] == 0) break;      // the frontier the next sweep would read is empty
-        if (k > n_nodes) break;                          // cannot happen: at most n_nodes layers
+        if (narrow) k = host_ctl[kSweep];
+        if (k < 0 || k > n_nodes + kSweepsPerSync) break;     // cannot happen: at most n_nodes layers
+        const int count = host_ctl[kCount0 + k % 3];         // the frontier the next sweep would read
+        if (count == 0) break;
+        // a narrow run that stopped on a non-empty frontier found it too wide: grid-wide sweeps next
+        narrow = !narrow && count <= kNarrowCap && (int64_t)count * mean_out <= kNarrowMaxEdges;
     }
     if (host_ctl[kAssigned] != n_nodes) return ASNN_ERR_CYCLE;
     *n_levels_out = host_ctl[kLevels];
@@ -454,7 +602,8 @@ extern "C" int asnn_required_set(int32_t n_nodes, int64_t n_edges, const int32_t
     ASNN_TRY(exclusive_scan_i32(w.out_ptr, w.out_ptr, (size_t)n_nodes + 1, w.scan_tmp, s));
     if (n_edges > 0) {
         hipLaunchKernelGGL(fill_out_kernel, dim3(blocks_for((size_t)n_edges, kThreads, 65535)), dim3(kThreads), 0, s,
-                           dst, src, n_edges, n_nodes, (const int32_t *)w.out_ptr, w.cursor, w.out_dst);
+                           dst, src, n_edges, n_nodes, (const int32_t *)w.out_ptr, w.cursor, (const int32_t *)nullptr,
+                           w.out_dst);
         ASNN_HIP_TRY(hipGetLastError());
     }
     if (n_outputs > 0) {

@@ -308,6 +308,60 @@ def test_error_codes_from_device_checks(amd):
     assert nl == 0
 
 
+def _stages_network(stages, rng):
+    """Layered DAG from a list of stage widths; stage s+1 nodes draw their sources from stage s
+    (`fan` sources each, or all of stage s when fan is None), plus a few from any earlier stage."""
+    src, dst = [], []
+    first = [0]
+    for width, _ in stages:
+        first.append(first[-1] + width)
+    for s in range(1, len(stages)):
+        width, fan = stages[s]
+        lo, hi = first[s - 1], first[s]
+        for v in range(first[s], first[s + 1]):
+            if fan is None:
+                picks = np.arange(lo, hi)
+            else:
+                picks = rng.integers(lo, hi, size=fan)
+                picks[0] = lo + (v % (hi - lo))           # every node of the stage below is used when widths allow
+            extra = rng.integers(0, hi, size=2)            # skip connections (and parallel ones)
+            for a in np.concatenate([picks, extra]):
+                src.append(int(a)); dst.append(v)
+    n = first[-1]
+    src, dst = np.array(src, np.int32), np.array(dst, np.int32)
+    relabel = rng.permutation(n).astype(np.int32)
+    order = rng.permutation(len(src))
+    return n, relabel[src][order], relabel[dst][order]
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_levels_across_narrow_and_wide_frontiers(amd, seed):
+    """Level assignment where the frontier keeps changing regime: narrow layers (swept by one
+    workgroup without leaving the device), layers wider than that workgroup keeps (grid-wide
+    sweeps), a node with 70000 outgoing connections, nodes with thousands of incoming ones (their
+    releases are added up per workgroup first), and back to a long narrow tail.  Bit-exact
+    against the oracle."""
+    rng = np.random.default_rng(seed)
+    stages = [(3, 0), (5, 2), (1, None), (6000, 1), (2, None), (40, 1), (1, None), (70000, 1), (3, None),
+              (300, 2), (1, None), (2500, 1), (2048, 3), (2049, 2), (7, 300)]
+    stages += [(int(w), 3) for w in rng.integers(1, 60, size=150)]
+    n, src, dst = _stages_network(stages, rng)
+    want, want_levels = oracle.levels(n, src, dst)
+    roots = np.flatnonzero(np.bincount(dst, minlength=n) == 0).astype(np.int32)
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    got, n_levels = amd.asnn_build_levels(n, t(src), t(dst), t(roots[:2]))
+    assert n_levels == want_levels == len(stages)
+    assert np.array_equal(got.cpu().numpy(), want)
+    # a cycle inside the narrow tail is still reported
+    hi = lo = np.flatnonzero(want == want_levels - 1)[0]
+    for _ in range(19):                                   # walk to an ancestor of hi, one level at a time
+        into = np.flatnonzero(dst == lo)
+        lo = src[into[np.argmax(want[src[into]])]]
+    with pytest.raises(amd.AsnnError) as e:
+        amd.asnn_build_levels(n, t(np.append(src, hi).astype(np.int32)), t(np.append(dst, lo).astype(np.int32)), t(roots[:2]))
+    assert e.value.code == -6
+
+
 FULL_COLUMNS = {1: None, 2: None, 3: 48, 4: 16, 5: 12}
 
 
