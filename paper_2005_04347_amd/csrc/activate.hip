@@ -31,6 +31,7 @@ namespace asnn {
 namespace {
 
 constexpr int kMixedBlock = 1024;                    // 16 wavefronts
+constexpr int kMaxDevices = 64;                       // per-device caches of launch parameters
 constexpr int kMixedWaves = kMixedBlock / kWave;
 constexpr int kMediumWaves = 8;                      // wavefronts per medium row in a level launch
 constexpr int kUnroll = 8;                           // row tiles in flight per wavefront
@@ -916,7 +917,11 @@ template <int VEC, int LPG, typename ACC>
 int launch_dataflow(const LevelArgs &a, const DataflowArgs &d) {
     const int vecs = a.B / VEC;
     const int tiles = (vecs + LPG - 1) / LPG;
-    static int per_cu = 0;       // resident 16-wave blocks per CU for this instantiation
+    static int per_cu_of[kMaxDevices] = {};       // resident 16-wave blocks per CU for this instantiation
+    int dev = 0;
+    ASNN_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return ASNN_ERR_NO_DEVICE;
+    int &per_cu = per_cu_of[dev];
     if (per_cu == 0) {
         int n = 0;
         ASNN_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dataflow_kernel<VEC, LPG, ACC, kUnroll>,
@@ -989,7 +994,6 @@ inline long long tiles_for_workgroup(int B) {
 // Dynamic LDS a staged workgroup needs; the packed network is staged when this fits what a
 // workgroup may take beside the static arrays of the kernel (partial sums: 16 x T accumulators).
 constexpr size_t kLdsDefaultPerWorkgroup = 64 * 1024;   // without raising the kernel attribute
-constexpr int kMaxDevices = 64;
 inline size_t staged_lds_bytes(int n_nodes, int64_t n_edges, int n_levels, int T) {
     return (((size_t)n_nodes * (size_t)T * 4 + 15) & ~(size_t)15) + 4 * ((size_t)n_nodes + 1) + 8 * (size_t)n_edges +
            4 * ((size_t)ASNN_CLASSES * (size_t)n_levels + 1);
