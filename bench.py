@@ -269,14 +269,19 @@ def main():
         per_col = (time.perf_counter() - t0) / probe.shape[1]
         cols = int(max(1, min(B, 15.0 / max(per_col, 1e-9))))
         Xs = np.ascontiguousarray(wl.X[:, :cols])
-        t0 = time.perf_counter()
-        oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, Xs)
-        cpu_s = time.perf_counter() - t0
+        # whole passes over the sample until about 10 s of CPU work are on the clock
+        cpu_s, passes = 0.0, 0
+        while cpu_s < 10.0 and passes < 1000:
+            t0 = time.perf_counter()
+            oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, Xs)
+            cpu_s += time.perf_counter() - t0
+            passes += 1
         out["cpu_baseline"] = {
-            "value": round(float(wl.n_edges) * cols / cpu_s / 1e9, 4), "unit": "G edge*samples/s", "cores": 1,
+            "value": round(float(wl.n_edges) * cols * passes / cpu_s / 1e9, 4), "unit": "G edge*samples/s", "cores": 1,
             "kind": "oracle",
             "sample": f"the same network, first {cols} of {B} batch columns (columns are independent), "
-                      f"{cpu_s:.2f} s single-threaded on {os.cpu_count()} visible host cores ({cpu_model()})",
+                      f"{passes} passes in {cpu_s:.2f} s single-threaded on {os.cpu_count()} visible host cores "
+                      f"({cpu_model()}); each pass includes building the oracle's adjacency lists",
         }
     print(json.dumps(out))
 
