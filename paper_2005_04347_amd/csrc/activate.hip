@@ -820,6 +820,29 @@ __global__ void stage_inputs_kernel(const int32_t *__restrict__ input_ids, const
     }
 }
 
+// Dataflow schedule: sensors and the reset of everything above level 0 (see dataflow_reset_kernel) in
+// one launch: the two write disjoint rows, and a launch costs a few microseconds.
+template <typename ACC>
+__global__ void dataflow_prologue_kernel(const int32_t *__restrict__ input_ids, const int32_t *__restrict__ inv_perm,
+                                         const float *__restrict__ X, float *__restrict__ V, int32_t n_inputs,
+                                         int32_t n_nodes, int B, int raw, unsigned int *v_begin, size_t n_values,
+                                         unsigned int *partial_words, size_t n_partial_words, DataflowCtl *ctl) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    const size_t first = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t total = (size_t)n_inputs * (size_t)B;
+    for (size_t i = first; i < total; i += stride) {
+        const int k = (int)(i / B), b = (int)(i % B);
+        const int32_t id = input_ids[k];
+        if (id < 0 || id >= n_nodes) continue;
+        const float x = X[i];
+        V[(size_t)inv_perm[id] * (size_t)B + b] = raw ? x : squash((ACC)x);
+    }
+    for (size_t i = first; i < n_values; i += stride) v_begin[i] = kNotReady;
+    for (size_t i = first; i < n_partial_words; i += stride) partial_words[i] = kNotReady;
+    if (blockIdx.x == 0 && threadIdx.x < 64)
+        reinterpret_cast<int *>(ctl)[threadIdx.x] = (threadIdx.x == 2) ? kCtlMagic : 0;
+}
+
 __global__ void extract_outputs_kernel(const int32_t *__restrict__ output_ids, const int32_t *__restrict__ inv_perm,
                                        const float *__restrict__ V, float *__restrict__ Y, int32_t n_outputs,
                                        int32_t n_nodes, int B) {
@@ -1224,7 +1247,7 @@ extern "C" int asnn_activate(const asnn_packed *packed, const int32_t *input_ids
         const int hb = level_ptr_host[0], mb = level_ptr_host[1], lb = level_ptr_host[2], le = level_ptr_host[3];
         if (le - hb != n_inputs)
             ASNN_TRY(f32 ? launch_level_any<float>(a, hb, mb, lb, le) : launch_level_any<double>(a, hb, mb, lb, le));
-        if (n_inputs > 0) {
+        if (n_inputs > 0 && !dataflow) {
             const unsigned blocks = blocks_for((size_t)n_inputs * (size_t)B, 256, 8192);
             if (f32)
                 hipLaunchKernelGGL(stage_inputs_kernel<float>, dim3(blocks), dim3(256), 0, s, input_ids,
@@ -1248,9 +1271,23 @@ extern "C" int asnn_activate(const asnn_packed *packed, const int32_t *input_ids
         }
         ActivateWorkspace ws = carve_activate(workspace, packed, B);
         const size_t n_values = (size_t)(n_nodes - first_row) * (size_t)B;
-        hipLaunchKernelGGL(dataflow_reset_kernel, dim3(blocks_for(n_values, 256 * 8, 4096)), dim3(256), 0, s,
-                           reinterpret_cast<unsigned int *>(V + (size_t)first_row * (size_t)B), n_values, ws.partials,
-                           ws.partial_bytes / sizeof(unsigned int), ws.ctl);
+        unsigned int *v_begin = reinterpret_cast<unsigned int *>(V + (size_t)first_row * (size_t)B);
+        const size_t n_partial_words = ws.partial_bytes / sizeof(unsigned int);
+        if (n_inputs > 0) {
+            const size_t most = n_values > (size_t)n_inputs * (size_t)B ? n_values : (size_t)n_inputs * (size_t)B;
+            const unsigned blocks = blocks_for(most, 256 * 8, 4096);
+            if (f32)
+                hipLaunchKernelGGL(dataflow_prologue_kernel<float>, dim3(blocks), dim3(256), 0, s, input_ids,
+                                   (const int32_t *)packed->inv_perm, X, V, n_inputs, n_nodes, B, raw, v_begin, n_values,
+                                   ws.partials, n_partial_words, ws.ctl);
+            else
+                hipLaunchKernelGGL(dataflow_prologue_kernel<double>, dim3(blocks), dim3(256), 0, s, input_ids,
+                                   (const int32_t *)packed->inv_perm, X, V, n_inputs, n_nodes, B, raw, v_begin, n_values,
+                                   ws.partials, n_partial_words, ws.ctl);
+        } else {
+            hipLaunchKernelGGL(dataflow_reset_kernel, dim3(blocks_for(n_values, 256 * 8, 4096)), dim3(256), 0, s, v_begin,
+                               n_values, ws.partials, n_partial_words, ws.ctl);
+        }
         ASNN_HIP_TRY(hipGetLastError());
         const int units_per_level = (packed->n_units - packed->first_unit + n_levels - 2) / (n_levels - 1);
         DataflowArgs d{packed->unit_ptr, packed->first_unit, (int)n_work, first_row,
