@@ -478,7 +478,10 @@ __global__ __launch_bounds__(kMixedBlock) void dataflow_kernel(const int32_t *__
                                                                 const float *__restrict__ w, float *V, uint32_t v_bytes,
                                                                 int B, const int32_t *__restrict__ unit_ptr,
                                                                 int first_unit, int n_work, int tiles, int first_row,
-                                                                DataflowCtl *ctl, void *partials, uint32_t partial_bytes) {
+                                                                DataflowCtl *ctl, void *partials, uint32_t partial_bytes,
+                                                                const int32_t *__restrict__ output_ids,
+                                                                const int32_t *__restrict__ inv_perm,
+                                                                float *__restrict__ Y, int n_outputs, int n_nodes) {
     constexpr int T = LPG * VEC;
     constexpr int E = T >= kWave ? T / kWave : 1;       // tile elements per lane when one wavefront holds the tile
     constexpr int EL = T >= kWave ? kWave : T;          // lanes that hold them
@@ -495,7 +498,32 @@ __global__ __launch_bounds__(kMixedBlock) void dataflow_kernel(const int32_t *__
         __syncthreads();
         const int q = s_claim;
         __syncthreads();
-        if (q >= n_work) return;                      // block-uniform
+        if (q >= n_work) {                            // block-uniform
+            // The items behind the last row copy the output rows to Y, 16 outputs (one per wavefront)
+            // by one tile each.  They wait for their rows like any other item (and are claimed last).
+            const int x = q - n_work;
+            if (x >= ((n_outputs + kMixedWaves - 1) / kMixedWaves) * tiles) return;
+            const int o = (x / tiles) * kMixedWaves + wave;
+            const int c = (x % tiles) * T + (lane % LPG) * VEC;
+            if (o < n_outputs && lane < LPG && c < B) {
+                const int32_t id = output_ids[o];
+                float out[VEC];
+                if (id >= 0 && id < n_nodes) {
+                    const int32_t row = inv_perm[id];
+                    const uint32_t off = ((uint32_t)row * (uint32_t)B + (uint32_t)c) * 4u;
+                    Patience patience;
+                    for (;;) {
+                        load_vec_device_scope<VEC>(vres, off, out);
+                        if (row < first_row || !shows_not_ready<VEC>(out) || !patience.again(ctl)) break;
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) out[j] = __builtin_nanf("");
+                }
+                store_vec<VEC>(Y + (size_t)o * (size_t)B + c, out);
+            }
+            continue;
+        }
         const int u = first_unit + q / tiles;
         const int tile = q % tiles;
         const int r0 = unit_ptr[u], r1 = unit_ptr[u + 1];
@@ -945,6 +973,9 @@ struct DataflowArgs {
     int units_per_level;     // average, for sizing the persistent grid
     void *partials;          // partial sums of split heavy rows
     uint32_t partial_bytes;
+    const int32_t *output_ids, *inv_perm;      // output rows are copied to Y by the same launch
+    float *Y;
+    int n_outputs, n_nodes;
 };
 
 template <int VEC, int LPG, typename ACC>
@@ -966,12 +997,13 @@ int launch_dataflow(const LevelArgs &a, const DataflowArgs &d) {
     // worth of units in flight is enough.
     long long blocks = (long long)d.cus * per_cu;
     const long long useful = 2LL * d.units_per_level * tiles + 32;
+    const long long items = (long long)d.n_work + (long long)((d.n_outputs + kMixedWaves - 1) / kMixedWaves) * tiles;
     if (blocks > useful) blocks = useful;
-    if (blocks > d.n_work) blocks = d.n_work;
+    if (blocks > items) blocks = items;
     if (blocks < 1) return ASNN_OK;
     hipLaunchKernelGGL((dataflow_kernel<VEC, LPG, ACC, kUnroll>), dim3((unsigned)blocks), dim3(kMixedBlock), 0, a.s,
                        a.row_ptr, a.col, a.w, a.V, d.v_bytes, a.B, d.unit_ptr, d.first_unit, d.n_work, tiles, d.first_row,
-                       d.ctl, d.partials, d.partial_bytes);
+                       d.ctl, d.partials, d.partial_bytes, d.output_ids, d.inv_perm, d.Y, d.n_outputs, d.n_nodes);
     ASNN_HIP_TRY(hipGetLastError());
     return ASNN_OK;
 }
@@ -1163,7 +1195,7 @@ int choose_schedule(const asnn_packed *packed, int32_t B, bool has_workspace, ui
     const long long n_work = (long long)(packed->n_units - packed->first_unit) * tiles_for(B);
     const bool possible = has_workspace && packed->unit_ptr && n_levels > 1 && packed->n_units > 0 &&
                           packed->first_unit >= 0 && packed->first_unit <= packed->n_units &&
-                          n_work > 0 && n_work < 0x7fffffffLL &&
+                          n_work > 0 && n_work < 0x3fffffffLL &&
                           (uint64_t)n_nodes * (uint64_t)B * 4u <= 0xffffffffull &&
                           carve_activate(nullptr, packed, B).partial_bytes <= 0xffffffffull;
     const bool workgroup_possible = packed->level_ptr != nullptr && tiles_for_workgroup(B) <= 0x7fffffffLL;
@@ -1269,6 +1301,8 @@ extern "C" int asnn_activate(const asnn_packed *packed, const int32_t *input_ids
             ASNN_HIP_TRY(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev));
             cus = n > 0 ? n : 1;
         }
+        // work items and output items are numbered by one 32-bit counter
+        if ((long long)((n_outputs + kMixedWaves - 1) / kMixedWaves) * tiles >= 0x3fffffffLL) return ASNN_ERR_SIZE;
         ActivateWorkspace ws = carve_activate(workspace, packed, B);
         const size_t n_values = (size_t)(n_nodes - first_row) * (size_t)B;
         unsigned int *v_begin = reinterpret_cast<unsigned int *>(V + (size_t)first_row * (size_t)B);
@@ -1292,8 +1326,10 @@ extern "C" int asnn_activate(const asnn_packed *packed, const int32_t *input_ids
         const int units_per_level = (packed->n_units - packed->first_unit + n_levels - 2) / (n_levels - 1);
         DataflowArgs d{packed->unit_ptr, packed->first_unit, (int)n_work, first_row,
                        (uint32_t)((uint64_t)n_nodes * (uint64_t)B * 4u), ws.ctl, cus, units_per_level,
-                       ws.partials, (uint32_t)ws.partial_bytes};
+                       ws.partials, (uint32_t)ws.partial_bytes, output_ids, packed->inv_perm, Y,
+                       (Y && n_outputs > 0) ? n_outputs : 0, n_nodes};
         ASNN_TRY(f32 ? launch_dataflow_any<float>(a, d) : launch_dataflow_any<double>(a, d));
+        return ASNN_OK;      // the outputs were copied by the same launch
     } else {
         for (int l = 1; l < n_levels; ++l) {
             const int32_t *lp = level_ptr_host + ASNN_CLASSES * l;
