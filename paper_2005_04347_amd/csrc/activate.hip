@@ -295,12 +295,15 @@ __device__ inline void store_vec_device_scope(__amdgpu_buffer_rsrc_t r, uint32_t
     if constexpr (VEC == 1) { __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, in[0]), r, byte_off, 0, kAuxDeviceScope); }
 }
 
+// True when one of the values still holds the not-ready pattern.  Written as a minimum over
+// (bits xor pattern) on purpose: an `or` over VEC comparisons was compiled into two dozen
+// instructions per tile, and a polling pass looks at 8 tiles.
 template <int VEC>
 __device__ inline bool shows_not_ready(const float (&v)[VEC]) {
-    bool r = false;
+    unsigned int m = __builtin_bit_cast(unsigned int, v[0]) ^ kNotReady;
 #pragma unroll
-    for (int j = 0; j < VEC; ++j) r = r || (__builtin_bit_cast(unsigned int, v[j]) == kNotReady);
-    return r;
+    for (int j = 1; j < VEC; ++j) m = min(m, __builtin_bit_cast(unsigned int, v[j]) ^ kNotReady);
+    return m == 0u;
 }
 
 // Partial sums of the chunks of a split heavy row travel through the workspace in ACC precision,
