@@ -134,14 +134,36 @@ def test_batch_widths_cover_every_lane_layout(amd, B):
     want = oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.X)
     net = None
     for sched in SCHEDULES:
-        net, V, _ = run_gpu(amd, wl, flags=sched, net=net)
+        net, V, Y = run_gpu(amd, wl, flags=sched, net=net)
         got = net.values_original_order(V).cpu().numpy()
         err = float(np.abs(got.astype(np.float64) - want).max())
         assert err <= TIGHT, (sched, err)
+        assert (Y.cpu().numpy() == got[wl.output_ids]).all(), sched
         _, V32, _ = run_gpu(amd, wl, flags=sched | amd.FLAG_ACC_F32, net=net)
         got32 = net.values_original_order(V32).cpu().numpy()
         err32 = float(np.abs(got32.astype(np.float64) - want).max())
         assert err32 <= TOL, (sched, err32)
+
+
+@pytest.mark.parametrize("B", [1, 5, 64, 130])
+def test_output_rows_of_any_level_and_bad_ids(amd, B):
+    """Y takes the rows of output_ids whatever their level: a sensor, a hidden node, a node listed
+    twice; an id outside [0, n_nodes) gives a row of NaN.  Every schedule, 20 outputs (more than
+    one group of 16 for the schedule that copies them with work items of its own)."""
+    wl = layered_skip(seed=11, n_nodes=400, n_inputs=12, n_outputs=5, n_levels=9, B=B, mean_extra_degree=6.0)
+    want = oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.X)
+    rng = np.random.default_rng(B)
+    ids = np.concatenate([wl.output_ids, wl.input_ids[:3], rng.integers(0, wl.n_nodes, size=9), [wl.output_ids[0]],
+                          [wl.n_nodes, -1]]).astype(np.int32)
+    net = amd.Network(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, ids)
+    for sched in (0, LEVELS, DATAFLOW, WORKGROUP):
+        V, Y = net.activate(wl.X, flags=sched)
+        net.check(B)
+        y = Y.cpu().numpy()
+        got = net.values_original_order(V).cpu().numpy()
+        assert np.abs(got.astype(np.float64) - want).max() <= TIGHT
+        assert (y[:-2] == got[ids[:-2]]).all(), sched
+        assert np.isnan(y[-2:]).all(), sched
 
 
 def _heavy_workload(B, seed=3):
