@@ -96,45 +96,65 @@ int exclusive_scan_i32(const int32_t *in, int32_t *out, size_t n, int32_t *tmp, 
 }
 
 // ------------------------------------------------------------ radix sort
+// One pass = a histogram per tile, an exclusive scan over (digit, tile), and a stable scatter.
+// A tile is 4096 pairs handled by a 256-thread block.  The scatter first brings the tile into
+// digit order in LDS and then writes it out, so that the pairs of one digit leave as one
+// contiguous run (16 pairs on average) instead of one by one.
 constexpr int kRadixBits = 8;
 constexpr int kRadixBins = 1 << kRadixBits;
-constexpr int kRadixRounds = 16;
-constexpr int kRadixTile = kWave * kRadixRounds;   // 1024 pairs per one-wave block
+constexpr int kRadixThreads = 256;
+constexpr int kRadixWaves = kRadixThreads / kWave;
+constexpr int kRadixRounds = 16;                                // pairs per thread
+constexpr int kRadixTile = kRadixThreads * kRadixRounds;       // 4096 pairs per block
+static_assert(kRadixBins == kRadixThreads, "the scatter gives every digit a thread of its own");
 
 // hist[d * nblocks + block] = number of keys of this block's tile with digit d.
-__global__ __launch_bounds__(kWave) void radix_hist_kernel(const uint32_t *__restrict__ keys, size_t n, int shift,
-                                                            int32_t *__restrict__ hist, unsigned nblocks) {
+__global__ __launch_bounds__(kRadixThreads) void radix_hist_kernel(const uint32_t *__restrict__ keys, size_t n, int shift,
+                                                                    int32_t *__restrict__ hist, unsigned nblocks) {
     __shared__ int bins[kRadixBins];
-    for (int d = threadIdx.x; d < kRadixBins; d += kWave) bins[d] = 0;
+    bins[threadIdx.x] = 0;
     __syncthreads();
     const size_t base = (size_t)blockIdx.x * kRadixTile;
 #pragma unroll 4
     for (int r = 0; r < kRadixRounds; ++r) {
-        size_t i = base + (size_t)r * kWave + threadIdx.x;
+        const size_t i = base + (size_t)r * kRadixThreads + threadIdx.x;
         if (i < n) atomicAdd(&bins[(keys[i] >> shift) & (kRadixBins - 1)], 1);
     }
     __syncthreads();
-    for (int d = threadIdx.x; d < kRadixBins; d += kWave) hist[(size_t)d * nblocks + blockIdx.x] = bins[d];
+    hist[(size_t)threadIdx.x * nblocks + blockIdx.x] = bins[threadIdx.x];
 }
 
-// Stable scatter: pairs of one tile keep their relative order inside a digit.
-__global__ __launch_bounds__(kWave) void radix_scatter_kernel(const uint32_t *__restrict__ keys_in,
-                                                               const uint32_t *__restrict__ vals_in,
-                                                               uint32_t *__restrict__ keys_out,
-                                                               uint32_t *__restrict__ vals_out, size_t n, int shift,
-                                                               const int32_t *__restrict__ offsets, unsigned nblocks) {
-    __shared__ int next[kRadixBins];
-    for (int d = threadIdx.x; d < kRadixBins; d += kWave) next[d] = offsets[(size_t)d * nblocks + blockIdx.x];
+// Stable scatter: pairs with the same digit keep their order.  Wavefront w takes pairs
+// [1024 w, 1024 (w+1)) of the tile, 64 at a time; a pair's place among the pairs of its digit is
+// (pairs of the digit in earlier wavefronts) + (in earlier rounds of its own) + (in lower lanes of
+// its round), the last from ballots.
+__global__ __launch_bounds__(kRadixThreads) void radix_scatter_kernel(const uint32_t *__restrict__ keys_in,
+                                                                       const uint32_t *__restrict__ vals_in,
+                                                                       uint32_t *__restrict__ keys_out,
+                                                                       uint32_t *__restrict__ vals_out, size_t n, int shift,
+                                                                       const int32_t *__restrict__ offsets, unsigned nblocks) {
+    __shared__ uint32_t s_key[kRadixTile], s_val[kRadixTile];
+    __shared__ int wave_count[kRadixWaves][kRadixBins];     // running count, later: pairs in earlier wavefronts
+    __shared__ int tile_start[kRadixBins];                  // first place of the digit inside the sorted tile
+    __shared__ int out_shift[kRadixBins];                   // global position = place inside the tile + this
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+#pragma unroll
+    for (int w = 0; w < kRadixWaves; ++w) wave_count[w][threadIdx.x] = 0;
     __syncthreads();
     const size_t base = (size_t)blockIdx.x * kRadixTile;
-    const int lane = threadIdx.x;
+    const size_t wave_base = base + (size_t)wave * (kRadixRounds * kWave);
     const unsigned long long below = (lane == 0) ? 0ull : (~0ull >> (kWave - lane));
+    uint32_t key[kRadixRounds], val[kRadixRounds];
+    int place[kRadixRounds];
+#pragma unroll
     for (int r = 0; r < kRadixRounds; ++r) {
-        const size_t i = base + (size_t)r * kWave + lane;
+        const size_t i = wave_base + (size_t)r * kWave + lane;
         const bool valid = i < n;
-        uint32_t key = 0, val = 0;
-        if (valid) { key = keys_in[i]; val = vals_in[i]; }
-        const int d = (key >> shift) & (kRadixBins - 1);
+        key[r] = 0;
+        val[r] = 0;
+        if (valid) { key[r] = keys_in[i]; val[r] = vals_in[i]; }
+        const int d = (key[r] >> shift) & (kRadixBins - 1);
         unsigned long long peers = __ballot(valid);
 #pragma unroll
         for (int b = 0; b < kRadixBits; ++b) {
@@ -142,17 +162,46 @@ __global__ __launch_bounds__(kWave) void radix_scatter_kernel(const uint32_t *__
             const unsigned long long m = __ballot(bit);
             peers &= bit ? m : ~m;
         }
-        const int rank = __popcll(peers & below);
-        const int count = __popcll(peers);
-        int start = 0;
-        if (valid) start = next[d];
-        __syncthreads();
-        if (valid && rank == 0) next[d] = start + count;
-        __syncthreads();
-        if (valid) {
-            keys_out[start + rank] = key;
-            vals_out[start + rank] = val;
+        // LDS accesses of one wavefront complete in program order: every lane has read the
+        // running count before the first lane of each digit adds this round's pairs to it
+        const int before = valid ? wave_count[wave][d] : 0;
+        if (valid && (peers & below) == 0) wave_count[wave][d] = before + __popcll(peers);
+        place[r] = before + __popcll(peers & below);
+    }
+    __syncthreads();
+    {   // thread d owns digit d: counts of the wavefronts -> exclusive prefix over them, digit totals -> tile_start
+        const int d = threadIdx.x;
+        int run = 0;
+#pragma unroll
+        for (int w = 0; w < kRadixWaves; ++w) {
+            const int c = wave_count[w][d];
+            wave_count[w][d] = run;
+            run += c;
         }
+        int total;
+        const int start = block_exclusive_scan(run, &total);
+        tile_start[d] = start;
+        out_shift[d] = offsets[(size_t)d * nblocks + blockIdx.x] - start;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < kRadixRounds; ++r) {
+        const size_t i = wave_base + (size_t)r * kWave + lane;
+        if (i < n) {
+            const int d = (key[r] >> shift) & (kRadixBins - 1);
+            const int p = tile_start[d] + wave_count[wave][d] + place[r];
+            s_key[p] = key[r];
+            s_val[p] = val[r];
+        }
+    }
+    __syncthreads();
+    const size_t left = n - base;
+    const int n_tile = left < (size_t)kRadixTile ? (int)left : kRadixTile;
+    for (int i = threadIdx.x; i < n_tile; i += kRadixThreads) {
+        const uint32_t k = s_key[i];
+        const size_t o = (size_t)(out_shift[(k >> shift) & (kRadixBins - 1)] + i);
+        keys_out[o] = k;
+        vals_out[o] = s_val[i];
     }
 }
 
@@ -173,11 +222,11 @@ int radix_sort_pairs_u32(uint32_t *keys_a, uint32_t *vals_a, uint32_t *keys_b, u
     int32_t *scan_tmp = tmp + align_up(hist_len * sizeof(int32_t)) / sizeof(int32_t);
     uint32_t *kin = keys_a, *vin = vals_a, *kout = keys_b, *vout = vals_b;
     for (int shift = 0; shift < bits; shift += kRadixBits) {
-        hipLaunchKernelGGL(radix_hist_kernel, dim3(nblocks), dim3(kWave), 0, s, (const uint32_t *)kin, n, shift, hist,
-                           nblocks);
+        hipLaunchKernelGGL(radix_hist_kernel, dim3(nblocks), dim3(kRadixThreads), 0, s, (const uint32_t *)kin, n, shift,
+                           hist, nblocks);
         ASNN_HIP_TRY(hipGetLastError());
         ASNN_TRY(exclusive_scan_i32(hist, hist, hist_len, scan_tmp, s));
-        hipLaunchKernelGGL(radix_scatter_kernel, dim3(nblocks), dim3(kWave), 0, s, (const uint32_t *)kin,
+        hipLaunchKernelGGL(radix_scatter_kernel, dim3(nblocks), dim3(kRadixThreads), 0, s, (const uint32_t *)kin,
                            (const uint32_t *)vin, kout, vout, n, shift, (const int32_t *)hist, nblocks);
         ASNN_HIP_TRY(hipGetLastError());
         uint32_t *t;
