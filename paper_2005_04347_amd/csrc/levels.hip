@@ -31,6 +31,7 @@ constexpr int kNarrowCap = 2048;       // frontier nodes it keeps in LDS
 constexpr int kNarrowMaxEdges = 4096;  // out-edges of one frontier it still takes alone (a single compute unit issues about one request per clock)
 constexpr int kNarrowBatch = 16;       // out-edges a thread releases per round trip
 constexpr int kNarrowBigOut = 64;      // out-degree from which the whole workgroup shares a node
+constexpr int64_t kSortedAdjacencyEdges = 1 << 21;     // connections from which the out-adjacency is sorted, not counted
 
 // Slots of the small control block in device memory.
 enum Ctl : int {
@@ -59,8 +60,10 @@ __device__ inline void wave_append(bool has, int32_t node, int32_t *__restrict__
     if (has) list[base + __popcll(mask & below)] = node;
 }
 
-__global__ void degree_kernel(const int32_t *__restrict__ src, const int32_t *__restrict__ dst, int64_t n_edges,
-                              int32_t n_nodes, int32_t *indeg, int32_t *outdeg, int *ctl) {
+// Checks every connection's ids and, with indeg given, counts the incoming connections of every
+// node (the counters the sweeps count down).
+__global__ void check_and_count_kernel(const int32_t *__restrict__ src, const int32_t *__restrict__ dst, int64_t n_edges,
+                                       int32_t n_nodes, int32_t *indeg, int *ctl) {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n_edges; e += stride) {
         const int32_t a = src[e], b = dst[e];
@@ -68,8 +71,7 @@ __global__ void degree_kernel(const int32_t *__restrict__ src, const int32_t *__
             flag_error(ctl, ASNN_ERR_INDEX);
             continue;
         }
-        atomicAdd(&indeg[b], 1);
-        atomicAdd(&outdeg[a], 1);
+        if (indeg != nullptr) atomicAdd(&indeg[b], 1);
     }
 }
 
@@ -83,19 +85,66 @@ __global__ void mark_inputs_kernel(const int32_t *__restrict__ input_ids, int32_
     if (indeg[v] != 0) flag_error(ctl, ASNN_ERR_INPUT_HAS_INEDGE);
 }
 
-// out_dst grouped by source; the order inside a group is irrelevant for levels.  With indeg given
-// (the final in-degrees: the sweeps have not started), destinations with many incoming
-// connections are marked with kHotBit.
-__global__ void fill_out_kernel(const int32_t *__restrict__ src, const int32_t *__restrict__ dst, int64_t n_edges,
+// Small networks: out-degree histogram with atomics (together with the in-degree counters), ...
+__global__ void degree_kernel(const int32_t *__restrict__ from, const int32_t *__restrict__ to, int64_t n_edges,
+                              int32_t n_nodes, int32_t *indeg, int32_t *outdeg, int *ctl) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n_edges; e += stride) {
+        const int32_t a = from[e], b = to[e];
+        if (a < 0 || a >= n_nodes || b < 0 || b >= n_nodes) {
+            flag_error(ctl, ASNN_ERR_INDEX);
+            continue;
+        }
+        if (indeg != nullptr) atomicAdd(&indeg[b], 1);
+        atomicAdd(&outdeg[a], 1);
+    }
+}
+
+// ... and a scatter into the lists with one returning atomic per connection (the order inside a
+// list is irrelevant for levels).  Hot destinations are marked as in out_pair_kernel.
+__global__ void fill_out_kernel(const int32_t *__restrict__ from, const int32_t *__restrict__ to, int64_t n_edges,
                                 int32_t n_nodes, const int32_t *__restrict__ out_ptr, int32_t *cursor,
                                 const int32_t *__restrict__ indeg, int32_t *__restrict__ out_dst) {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n_edges; e += stride) {
-        const int32_t a = src[e], b = dst[e];
+        const int32_t a = from[e], b = to[e];
         if (a < 0 || a >= n_nodes || b < 0 || b >= n_nodes) continue;   // already flagged
         const int32_t pos = out_ptr[a] + atomicAdd(&cursor[a], 1);
         out_dst[pos] = (indeg != nullptr && indeg[b] >= kHotIndegree) ? (b | kHotBit) : b;
     }
+}
+
+// Large networks: the out-adjacency comes from a stable sort of (source, destination) pairs by
+// source instead (from a few million connections on, two atomics per connection cost more than
+// the sort passes; below, the sort's extra launches do).  Key = source, value = destination; with indeg given (the final in-degrees: the sweeps
+// have not started), destinations with many incoming connections are marked with kHotBit.  A
+// connection with an id out of range (already flagged) is filed under node 0 -> node 0, so that
+// nothing reads out of bounds before the host sees the error.
+__global__ void out_pair_kernel(const int32_t *__restrict__ from, const int32_t *__restrict__ to, int64_t n_edges,
+                                int32_t n_nodes, const int32_t *__restrict__ indeg, uint32_t *__restrict__ keys,
+                                uint32_t *__restrict__ vals) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n_edges; e += stride) {
+        int32_t a = from[e], b = to[e];
+        if (a < 0 || a >= n_nodes || b < 0 || b >= n_nodes) a = b = 0;
+        keys[e] = (uint32_t)a;
+        vals[e] = (uint32_t)((indeg != nullptr && indeg[b] >= kHotIndegree) ? (b | kHotBit) : b);
+    }
+}
+
+// Run boundaries of the sorted keys: first[k] = where the run of key k starts ...
+__global__ void run_heads_kernel(const uint32_t *__restrict__ keys, int64_t n_edges, int32_t *__restrict__ first) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_edges; i += stride)
+        if (i == 0 || keys[i - 1] != keys[i]) first[keys[i]] = (int32_t)i;
+}
+
+// ... and count[k] = its length (count is zero for keys without a run).
+__global__ void run_lengths_kernel(const uint32_t *__restrict__ keys, int64_t n_edges, const int32_t *__restrict__ first,
+                                   int32_t *__restrict__ count) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_edges; i += stride)
+        if (i == n_edges - 1 || keys[i + 1] != keys[i]) count[keys[i]] = (int32_t)(i + 1) - first[keys[i]];
 }
 
 // Level 0 = every node without an incoming connection.
@@ -361,7 +410,8 @@ __global__ __launch_bounds__(kNarrowThreads) void narrow_sweeps_kernel(int k0, c
 
 struct LevelsWorkspace {
     int *ctl;
-    int32_t *indeg, *out_ptr, *cursor, *is_input, *out_dst, *frontier_a, *frontier_b, *scan_tmp;
+    int32_t *indeg, *out_ptr, *first, *is_input, *frontier_a, *frontier_b, *scan_tmp, *radix_tmp;
+    uint32_t *keys_a, *keys_b, *vals_a, *vals_b;     // sort buffers; the out-adjacency ends up in one of the vals
     size_t bytes;
 };
 
@@ -372,14 +422,58 @@ static LevelsWorkspace carve_levels(void *ws, int32_t n_nodes, int64_t n_edges) 
     w.ctl = c.take<int>(kCtlInts);
     w.indeg = c.take<int32_t>(n + 1);
     w.out_ptr = c.take<int32_t>(n + 1);
-    w.cursor = c.take<int32_t>(n + 1);
+    w.first = c.take<int32_t>(n + 1);
     w.is_input = c.take<int32_t>(n + 1);
-    w.out_dst = c.take<int32_t>(e + 1);
+    w.keys_a = c.take<uint32_t>(e + 1);
+    w.keys_b = c.take<uint32_t>(e + 1);
+    w.vals_a = c.take<uint32_t>(e + 1);
+    w.vals_b = c.take<uint32_t>(e + 1);
     w.frontier_a = c.take<int32_t>(n + 1);
     w.frontier_b = c.take<int32_t>(n + 1);
     w.scan_tmp = c.take<int32_t>(scan_tmp_ints(n + 1));
+    w.radix_tmp = c.take<int32_t>(radix_tmp_ints(e + 1));
     w.bytes = c.off;
     return w;
+}
+
+// Groups the connections from[e] -> to[e] by `from`: w.out_ptr[n_nodes + 1] and, through *adjacent,
+// the `to` ids of each node, contiguous (in edge-list order when they were sorted).  count_incoming also fills w.indeg
+// (and marks hot destinations in the lists).  Clears the control block and the per-node arrays first.
+static int group_connections(const LevelsWorkspace &w, int32_t n_nodes, int64_t n_edges, const int32_t *from,
+                             const int32_t *to, bool count_incoming, hipStream_t s, const int32_t **adjacent) {
+    // ctl, indeg, out_ptr, first and is_input are adjacent: clear them in one go.
+    const size_t clear_bytes = (size_t)((char *)w.keys_a - (char *)w.ctl);
+    ASNN_HIP_TRY(hipMemsetAsync(w.ctl, 0, clear_bytes, s));
+    *adjacent = reinterpret_cast<const int32_t *>(w.vals_a);
+    int32_t *indeg = count_incoming ? w.indeg : (int32_t *)nullptr;
+    const dim3 grid(blocks_for((size_t)(n_edges > 0 ? n_edges : 1), kThreads, 65535)), block(kThreads);
+    if (n_edges > 0 && n_edges < kSortedAdjacencyEdges) {
+        hipLaunchKernelGGL(degree_kernel, grid, block, 0, s, from, to, n_edges, n_nodes, indeg, w.out_ptr, w.ctl);
+        ASNN_HIP_TRY(hipGetLastError());
+        ASNN_TRY(exclusive_scan_i32(w.out_ptr, w.out_ptr, (size_t)n_nodes + 1, w.scan_tmp, s));
+        hipLaunchKernelGGL(fill_out_kernel, grid, block, 0, s, from, to, n_edges, n_nodes, (const int32_t *)w.out_ptr,
+                           w.first, (const int32_t *)indeg, reinterpret_cast<int32_t *>(w.vals_a));
+        ASNN_HIP_TRY(hipGetLastError());
+        return ASNN_OK;
+    }
+    if (n_edges > 0) {
+        hipLaunchKernelGGL(check_and_count_kernel, grid, block, 0, s, from, to, n_edges, n_nodes, indeg, w.ctl);
+        ASNN_HIP_TRY(hipGetLastError());
+        hipLaunchKernelGGL(out_pair_kernel, grid, block, 0, s, from, to, n_edges, n_nodes, (const int32_t *)indeg, w.keys_a,
+                           w.vals_a);
+        ASNN_HIP_TRY(hipGetLastError());
+        uint32_t *ks = nullptr, *vs = nullptr;
+        ASNN_TRY(radix_sort_pairs_u32(w.keys_a, w.vals_a, w.keys_b, w.vals_b, (size_t)n_edges,
+                                      bits_for((uint64_t)n_nodes - 1), w.radix_tmp, s, &ks, &vs));
+        *adjacent = reinterpret_cast<const int32_t *>(vs);
+        hipLaunchKernelGGL(run_heads_kernel, grid, block, 0, s, (const uint32_t *)ks, n_edges, w.first);
+        ASNN_HIP_TRY(hipGetLastError());
+        hipLaunchKernelGGL(run_lengths_kernel, grid, block, 0, s, (const uint32_t *)ks, n_edges, (const int32_t *)w.first,
+                           w.out_ptr);
+        ASNN_HIP_TRY(hipGetLastError());
+    }
+    // out-degree histogram -> out_ptr (n_nodes + 1 entries; the extra zero yields the total)
+    return exclusive_scan_i32(w.out_ptr, w.out_ptr, (size_t)n_nodes + 1, w.scan_tmp, s);
 }
 
 }  // namespace asnn
@@ -408,26 +502,11 @@ extern "C" int asnn_build_levels(int32_t n_nodes, int64_t n_edges, const int32_t
     hipStream_t s = static_cast<hipStream_t>(stream);
     LevelsWorkspace w = carve_levels(workspace, n_nodes, n_edges);
 
-    // ctl, indeg, out_ptr, cursor and is_input are adjacent: clear them in one go.
-    const size_t clear_bytes = (size_t)((char *)w.out_dst - (char *)w.ctl);
-    ASNN_HIP_TRY(hipMemsetAsync(w.ctl, 0, clear_bytes, s));
-
-    if (n_edges > 0) {
-        hipLaunchKernelGGL(degree_kernel, dim3(blocks_for((size_t)n_edges, kThreads, 65535)), dim3(kThreads), 0, s, src,
-                           dst, n_edges, n_nodes, w.indeg, w.out_ptr, w.ctl);
-        ASNN_HIP_TRY(hipGetLastError());
-    }
+    const int32_t *out_dst = nullptr;
+    ASNN_TRY(group_connections(w, n_nodes, n_edges, src, dst, true, s, &out_dst));
     if (n_inputs > 0) {
         hipLaunchKernelGGL(mark_inputs_kernel, dim3(blocks_for((size_t)n_inputs, kThreads)), dim3(kThreads), 0, s,
                            input_ids, n_inputs, n_nodes, (const int32_t *)w.indeg, w.is_input, w.ctl);
-        ASNN_HIP_TRY(hipGetLastError());
-    }
-    // out-degree histogram -> out_ptr (n_nodes + 1 entries; the extra zero yields the total)
-    ASNN_TRY(exclusive_scan_i32(w.out_ptr, w.out_ptr, (size_t)n_nodes + 1, w.scan_tmp, s));
-    if (n_edges > 0) {
-        hipLaunchKernelGGL(fill_out_kernel, dim3(blocks_for((size_t)n_edges, kThreads, 65535)), dim3(kThreads), 0, s,
-                           src, dst, n_edges, n_nodes, (const int32_t *)w.out_ptr, w.cursor, (const int32_t *)w.indeg,
-                           w.out_dst);
         ASNN_HIP_TRY(hipGetLastError());
     }
     hipLaunchKernelGGL(first_frontier_kernel, dim3(blocks_for((size_t)n_nodes, 4 * kThreads, 2048)), dim3(kThreads), 0, s,
@@ -445,14 +524,14 @@ extern "C" int asnn_build_levels(int32_t n_nodes, int64_t n_edges, const int32_t
     for (;;) {
         if (narrow) {
             hipLaunchKernelGGL(narrow_sweeps_kernel, dim3(1), dim3(kNarrowThreads), 0, s, k, (const int32_t *)w.out_ptr,
-                               (const int32_t *)w.out_dst, w.indeg, level_out, w.frontier_a, w.frontier_b, w.ctl);
+                               out_dst, w.indeg, level_out, w.frontier_a, w.frontier_b, w.ctl);
             ASNN_HIP_TRY(hipGetLastError());
         } else {
             for (int i = 0; i < kSweepsPerSync; ++i, ++k) {
                 const int32_t *fin = (k & 1) ? w.frontier_b : w.frontier_a;
                 int32_t *fout = (k & 1) ? w.frontier_a : w.frontier_b;
                 hipLaunchKernelGGL(sweep_kernel, dim3(kSweepBlocks), dim3(kThreads), 0, s, k, (const int32_t *)w.out_ptr,
-                                   (const int32_t *)w.out_dst, w.indeg, level_out, fin, fout, w.ctl);
+                                   out_dst, w.indeg, level_out, fin, fout, w.ctl);
                 ASNN_HIP_TRY(hipGetLastError());
             }
         }
@@ -590,22 +669,10 @@ extern "C" int asnn_required_set(int32_t n_nodes, int64_t n_edges, const int32_t
         return ASNN_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     LevelsWorkspace w = carve_levels(workspace, n_nodes, n_edges);
-    const size_t clear_bytes = (size_t)((char *)w.out_dst - (char *)w.ctl);
-    ASNN_HIP_TRY(hipMemsetAsync(w.ctl, 0, clear_bytes, s));
     ASNN_HIP_TRY(hipMemsetAsync(required_out, 0, sizeof(int32_t) * (size_t)n_nodes, s));
-    if (n_edges > 0) {
-        // transposed: count and group the connections by destination
-        hipLaunchKernelGGL(degree_kernel, dim3(blocks_for((size_t)n_edges, kThreads, 65535)), dim3(kThreads), 0, s, dst,
-                           src, n_edges, n_nodes, w.indeg, w.out_ptr, w.ctl);
-        ASNN_HIP_TRY(hipGetLastError());
-    }
-    ASNN_TRY(exclusive_scan_i32(w.out_ptr, w.out_ptr, (size_t)n_nodes + 1, w.scan_tmp, s));
-    if (n_edges > 0) {
-        hipLaunchKernelGGL(fill_out_kernel, dim3(blocks_for((size_t)n_edges, kThreads, 65535)), dim3(kThreads), 0, s,
-                           dst, src, n_edges, n_nodes, (const int32_t *)w.out_ptr, w.cursor, (const int32_t *)nullptr,
-                           w.out_dst);
-        ASNN_HIP_TRY(hipGetLastError());
-    }
+    // transposed: the connections grouped by destination
+    const int32_t *in_src = nullptr;
+    ASNN_TRY(group_connections(w, n_nodes, n_edges, dst, src, false, s, &in_src));
     if (n_outputs > 0) {
         hipLaunchKernelGGL(seed_outputs_kernel, dim3(blocks_for((size_t)n_outputs, kThreads)), dim3(kThreads), 0, s,
                            output_ids, n_outputs, n_nodes, required_out, w.frontier_a, w.ctl);
@@ -618,7 +685,7 @@ extern "C" int asnn_required_set(int32_t n_nodes, int64_t n_edges, const int32_t
             const int32_t *fin = (k & 1) ? w.frontier_b : w.frontier_a;
             int32_t *fout = (k & 1) ? w.frontier_a : w.frontier_b;
             hipLaunchKernelGGL(reach_sweep_kernel, dim3(kSweepBlocks), dim3(kThreads), 0, s, k,
-                               (const int32_t *)w.out_ptr, (const int32_t *)w.out_dst, required_out, fin, fout, w.ctl);
+                               (const int32_t *)w.out_ptr, in_src, required_out, fin, fout, w.ctl);
             ASNN_HIP_TRY(hipGetLastError());
         }
         ASNN_HIP_TRY(hipMemcpyAsync(host_ctl, w.ctl, sizeof(host_ctl), hipMemcpyDeviceToHost, s));

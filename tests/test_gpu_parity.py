@@ -166,6 +166,22 @@ def test_output_rows_of_any_level_and_bad_ids(amd, B):
         assert np.isnan(y[-2:]).all(), sched
 
 
+def test_required_set_on_a_sorted_adjacency(amd):
+    """Networks with millions of connections group them with a sort instead of a counting pass:
+    the required set of the 16 M-connection workload, bit-exact, and its levels once more."""
+    wl = make_config(4, "full")
+    dev = "cuda:0"
+    src = torch.from_numpy(wl.src).to(dev); dst = torch.from_numpy(wl.dst).to(dev)
+    outs = torch.from_numpy(wl.output_ids[:3]).to(dev)
+    req, n_req = amd.asnn_required_set(wl.n_nodes, src, dst, outs)
+    want = oracle.required(wl.n_nodes, wl.src, wl.dst, wl.output_ids[:3])
+    assert (req.cpu().numpy().astype(bool) == want).all() and n_req == int(want.sum())
+    assert 0 < n_req < wl.n_nodes
+    level, n_levels = amd.asnn_build_levels(wl.n_nodes, src, dst, torch.from_numpy(wl.input_ids).to(dev))
+    lv, nl = oracle.levels(wl.n_nodes, wl.src, wl.dst)
+    assert n_levels == nl and (level.cpu().numpy() == lv).all()
+
+
 def _heavy_workload(B, seed=3):
     """A few rows with in-degree far above the heavy threshold (parallel edges
     included), mixed with light rows and a non-sensor root."""
