@@ -81,6 +81,11 @@ int radix_sort_pairs_u32(uint32_t *keys_a, uint32_t *vals_a, uint32_t *keys_b, u
                          size_t n, int bits, int32_t *tmp, hipStream_t s,
                          uint32_t **keys_sorted, uint32_t **vals_sorted);
 
+// Runs of equal keys in a sorted key array (every key < the length of first/count):
+// first[k] = index of the first occurrence of k, count[k] = number of occurrences.  Entries of
+// keys that do not occur are left as they are (the caller clears count beforehand).
+int sorted_run_lengths(const uint32_t *keys, size_t n, int32_t *first, int32_t *count, hipStream_t s);
+
 inline int bits_for(uint64_t max_value) {   // number of bits needed to hold max_value
     int b = 1;
     while (b < 32 && (max_value >> b) != 0) ++b;

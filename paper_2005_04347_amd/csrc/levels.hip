@@ -132,21 +132,6 @@ __global__ void out_pair_kernel(const int32_t *__restrict__ from, const int32_t 
     }
 }
 
-// Run boundaries of the sorted keys: first[k] = where the run of key k starts ...
-__global__ void run_heads_kernel(const uint32_t *__restrict__ keys, int64_t n_edges, int32_t *__restrict__ first) {
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_edges; i += stride)
-        if (i == 0 || keys[i - 1] != keys[i]) first[keys[i]] = (int32_t)i;
-}
-
-// ... and count[k] = its length (count is zero for keys without a run).
-__global__ void run_lengths_kernel(const uint32_t *__restrict__ keys, int64_t n_edges, const int32_t *__restrict__ first,
-                                   int32_t *__restrict__ count) {
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_edges; i += stride)
-        if (i == n_edges - 1 || keys[i + 1] != keys[i]) count[keys[i]] = (int32_t)(i + 1) - first[keys[i]];
-}
-
 // Level 0 = every node without an incoming connection.
 // Grid-stride over the nodes; a workgroup collects its roots in LDS and appends them with one
 // atomic on the frontier size (see sweep_kernel).
@@ -466,11 +451,7 @@ static int group_connections(const LevelsWorkspace &w, int32_t n_nodes, int64_t 
         ASNN_TRY(radix_sort_pairs_u32(w.keys_a, w.vals_a, w.keys_b, w.vals_b, (size_t)n_edges,
                                       bits_for((uint64_t)n_nodes - 1), w.radix_tmp, s, &ks, &vs));
         *adjacent = reinterpret_cast<const int32_t *>(vs);
-        hipLaunchKernelGGL(run_heads_kernel, grid, block, 0, s, (const uint32_t *)ks, n_edges, w.first);
-        ASNN_HIP_TRY(hipGetLastError());
-        hipLaunchKernelGGL(run_lengths_kernel, grid, block, 0, s, (const uint32_t *)ks, n_edges, (const int32_t *)w.first,
-                           w.out_ptr);
-        ASNN_HIP_TRY(hipGetLastError());
+        ASNN_TRY(sorted_run_lengths(ks, (size_t)n_edges, w.first, w.out_ptr, s));
     }
     // out-degree histogram -> out_ptr (n_nodes + 1 entries; the extra zero yields the total)
     return exclusive_scan_i32(w.out_ptr, w.out_ptr, (size_t)n_nodes + 1, w.scan_tmp, s);

@@ -9,7 +9,7 @@
 // only rows below its own range.
 //
 // Everything is built from two stable radix sorts (nodes by level key, edges
-// by packed destination) and prefix sums, so the packed arrays are a
+// by destination) and prefix sums, so the packed arrays are a
 // deterministic function of the input: a node's connections keep their
 // edge-list order; nodes are ordered by level, in-degree class, short-row
 // flag, then original id.
@@ -95,6 +95,47 @@ __global__ void edge_key_kernel(const int32_t *__restrict__ dst, const int32_t *
     }
 }
 
+// Large networks: the connections are sorted by ORIGINAL destination before the packed order is
+// known, which also yields the in-degrees (run lengths) without an atomic per connection; a
+// node's run is then moved as a whole to its packed row.  Same checks as indegree_kernel; a
+// connection with a bad id is filed under node 0 (the error is already flagged).
+__global__ void edge_key_by_id_kernel(const int32_t *__restrict__ src, const int32_t *__restrict__ dst,
+                                      const int32_t *__restrict__ level, int64_t n_edges, int32_t n_nodes,
+                                      int32_t n_levels, uint32_t *__restrict__ keys, uint32_t *__restrict__ vals, int *err) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n_edges; e += stride) {
+        const int32_t a = src[e];
+        int32_t b = dst[e];
+        if (a < 0 || a >= n_nodes || b < 0 || b >= n_nodes) {
+            flag_error(err, ASNN_ERR_INDEX);
+            b = 0;
+        } else {
+            const int32_t la = level[a], lb = level[b];
+            if (la < 0 || la >= n_levels || lb < 0 || lb >= n_levels) flag_error(err, ASNN_ERR_INDEX);
+            else if (la >= lb) flag_error(err, ASNN_ERR_LEVEL_ORDER);
+        }
+        keys[e] = (uint32_t)b;
+        vals[e] = (uint32_t)e;
+    }
+}
+
+// sorted position i (destination sorted_dst[i], i - first[destination] connections of the same
+// node before it) -> packed position row_ptr[packed row of the destination] + that offset.
+__global__ void place_edges_kernel(const uint32_t *__restrict__ sorted_dst, const uint32_t *__restrict__ sorted_edge,
+                                   const int32_t *__restrict__ first, const int32_t *__restrict__ row_ptr,
+                                   const int32_t *__restrict__ src, const float *__restrict__ w,
+                                   const int32_t *__restrict__ inv_perm, int64_t n_edges, int32_t n_nodes,
+                                   int32_t *__restrict__ col, float *__restrict__ w_packed) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_edges; i += stride) {
+        const uint32_t b = sorted_dst[i], e = sorted_edge[i];
+        const int64_t p = (int64_t)row_ptr[inv_perm[b]] + (i - first[b]);
+        const int32_t a = src[e];
+        col[p] = (a >= 0 && a < n_nodes) ? inv_perm[a] : 0;
+        w_packed[p] = w[e];
+    }
+}
+
 __global__ void gather_edges_kernel(const uint32_t *__restrict__ sorted_edge, const int32_t *__restrict__ src,
                                     const float *__restrict__ w, const int32_t *__restrict__ inv_perm, int64_t n_edges,
                                     int32_t n_nodes, int32_t *__restrict__ col, float *__restrict__ w_packed) {
@@ -149,10 +190,15 @@ __global__ void unit_counts_kernel(const int32_t *__restrict__ first_unit, const
 
 struct PackWorkspace {
     int *err;
-    int32_t *indeg, *packed_deg, *seg_units, *tmp;
-    uint32_t *keys_a, *vals_a, *keys_b, *vals_b;
+    int32_t *indeg, *packed_deg, *seg_units, *tmp, *first;
+    uint32_t *keys_a, *vals_a, *keys_b, *vals_b;            // the edge sort (and, for small networks, the node sort before it)
+    uint32_t *node_keys_a, *node_vals_a, *node_keys_b, *node_vals_b;     // large networks: the node sort has buffers of its own
     size_t bytes;
 };
+
+// Connections from which the edges are sorted before the packed order is known (below, the
+// in-degree count with one atomic per connection is cheaper than the bookkeeping).
+constexpr int64_t kSortFirstEdges = 1 << 21;
 
 static PackWorkspace carve_pack(void *ws, int32_t n_nodes, int64_t n_edges) {
     Carver c(ws);
@@ -167,6 +213,12 @@ static PackWorkspace carve_pack(void *ws, int32_t n_nodes, int64_t n_edges) {
     w.vals_a = c.take<uint32_t>(m);
     w.keys_b = c.take<uint32_t>(m);
     w.vals_b = c.take<uint32_t>(m);
+    const size_t own = n_edges >= kSortFirstEdges ? n + 1 : 0;
+    w.node_keys_a = c.take<uint32_t>(own);
+    w.node_vals_a = c.take<uint32_t>(own);
+    w.node_keys_b = c.take<uint32_t>(own);
+    w.node_vals_b = c.take<uint32_t>(own);
+    w.first = c.take<int32_t>(own);
     const size_t t1 = radix_tmp_ints(m), t2 = scan_tmp_ints(n + 1);
     w.tmp = c.take<int32_t>(t1 > t2 ? t1 : t2);
     w.bytes = c.off;
@@ -204,18 +256,29 @@ extern "C" int asnn_pack_csr(const int32_t *src, const int32_t *dst, const float
     const int32_t n_keys = ASNN_CLASSES * n_levels;
 
     ASNN_HIP_TRY(hipMemsetAsync(ws.err, 0, (size_t)((char *)ws.packed_deg - (char *)ws.err), s));   // err + indeg
-    if (n_edges > 0) {
-        hipLaunchKernelGGL(indegree_kernel, dim3(blocks_for((size_t)n_edges, kThreads, 65535)), dim3(kThreads), 0, s,
-                           src, dst, level, n_edges, n_nodes, n_levels, ws.indeg, ws.err);
+    const bool sort_first = n_edges >= kSortFirstEdges;
+    const unsigned eb = blocks_for((size_t)(n_edges > 0 ? n_edges : 1), kThreads, 65535);
+    uint32_t *edge_keys = nullptr, *edge_ids = nullptr;      // sort_first: connections sorted by original destination
+    if (sort_first) {
+        hipLaunchKernelGGL(edge_key_by_id_kernel, dim3(eb), dim3(kThreads), 0, s, src, dst, level, n_edges, n_nodes,
+                           n_levels, ws.keys_a, ws.vals_a, ws.err);
+        ASNN_HIP_TRY(hipGetLastError());
+        ASNN_TRY(radix_sort_pairs_u32(ws.keys_a, ws.vals_a, ws.keys_b, ws.vals_b, (size_t)n_edges,
+                                      bits_for((uint64_t)n_nodes - 1), ws.tmp, s, &edge_keys, &edge_ids));
+        ASNN_TRY(sorted_run_lengths(edge_keys, (size_t)n_edges, ws.first, ws.indeg, s));
+    } else if (n_edges > 0) {
+        hipLaunchKernelGGL(indegree_kernel, dim3(eb), dim3(kThreads), 0, s, src, dst, level, n_edges, n_nodes, n_levels,
+                           ws.indeg, ws.err);
         ASNN_HIP_TRY(hipGetLastError());
     }
     // nodes: stable sort by (level, in-degree class) key
+    uint32_t *nka = sort_first ? ws.node_keys_a : ws.keys_a, *nva = sort_first ? ws.node_vals_a : ws.vals_a;
+    uint32_t *nkb = sort_first ? ws.node_keys_b : ws.keys_b, *nvb = sort_first ? ws.node_vals_b : ws.vals_b;
     hipLaunchKernelGGL(node_key_kernel, dim3(blocks_for(n, kThreads)), dim3(kThreads), 0, s, level,
-                       (const int32_t *)ws.indeg, n_nodes, n_levels, (int32_t)(n_edges / n_nodes), ws.keys_a, ws.vals_a, ws.err);
+                       (const int32_t *)ws.indeg, n_nodes, n_levels, (int32_t)(n_edges / n_nodes), nka, nva, ws.err);
     ASNN_HIP_TRY(hipGetLastError());
     uint32_t *ks, *vs;
-    ASNN_TRY(radix_sort_pairs_u32(ws.keys_a, ws.vals_a, ws.keys_b, ws.vals_b, n, bits_for((uint64_t)n_keys << kRankBits), ws.tmp, s,
-                                  &ks, &vs));
+    ASNN_TRY(radix_sort_pairs_u32(nka, nva, nkb, nvb, n, bits_for((uint64_t)n_keys << kRankBits), ws.tmp, s, &ks, &vs));
     hipLaunchKernelGGL(permutation_kernel, dim3(blocks_for(n + 1, kThreads)), dim3(kThreads), 0, s,
                        (const uint32_t *)vs, (const int32_t *)ws.indeg, n_nodes, perm, inv_perm, ws.packed_deg);
     ASNN_HIP_TRY(hipGetLastError());
@@ -238,8 +301,12 @@ extern "C" int asnn_pack_csr(const int32_t *src, const int32_t *dst, const float
     ASNN_HIP_TRY(hipMemcpyAsync(host_units, ws.err + 2, 3 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
 
     // edges: stable sort by packed destination keeps each node's edge-list order
-    if (n_edges > 0) {
-        const unsigned eb = blocks_for((size_t)n_edges, kThreads, 65535);
+    if (sort_first) {
+        hipLaunchKernelGGL(place_edges_kernel, dim3(eb), dim3(kThreads), 0, s, (const uint32_t *)edge_keys,
+                           (const uint32_t *)edge_ids, (const int32_t *)ws.first, (const int32_t *)row_ptr, src, w,
+                           (const int32_t *)inv_perm, n_edges, n_nodes, col, w_packed);
+        ASNN_HIP_TRY(hipGetLastError());
+    } else if (n_edges > 0) {
         hipLaunchKernelGGL(edge_key_kernel, dim3(eb), dim3(kThreads), 0, s, dst, (const int32_t *)inv_perm, n_edges,
                            n_nodes, ws.keys_a, ws.vals_a);
         ASNN_HIP_TRY(hipGetLastError());

@@ -205,6 +205,32 @@ __global__ __launch_bounds__(kRadixThreads) void radix_scatter_kernel(const uint
     }
 }
 
+// ------------------------------------------------------------ runs of sorted keys
+// first[k] = where the run of key k starts in the sorted keys ...
+__global__ void run_heads_kernel(const uint32_t *__restrict__ keys, size_t n, int32_t *__restrict__ first) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
+        if (i == 0 || keys[i - 1] != keys[i]) first[keys[i]] = (int32_t)i;
+}
+
+// ... and count[k] = its length.
+__global__ void run_lengths_kernel(const uint32_t *__restrict__ keys, size_t n, const int32_t *__restrict__ first,
+                                   int32_t *__restrict__ count) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
+        if (i == n - 1 || keys[i + 1] != keys[i]) count[keys[i]] = (int32_t)(i + 1) - first[keys[i]];
+}
+
+int sorted_run_lengths(const uint32_t *keys, size_t n, int32_t *first, int32_t *count, hipStream_t s) {
+    if (n == 0) return ASNN_OK;
+    const dim3 grid(blocks_for(n, 256, 65535)), block(256);
+    hipLaunchKernelGGL(run_heads_kernel, grid, block, 0, s, keys, n, first);
+    ASNN_HIP_TRY(hipGetLastError());
+    hipLaunchKernelGGL(run_lengths_kernel, grid, block, 0, s, keys, n, (const int32_t *)first, count);
+    ASNN_HIP_TRY(hipGetLastError());
+    return ASNN_OK;
+}
+
 size_t radix_tmp_ints(size_t n) {
     const size_t nblocks = (n + kRadixTile - 1) / kRadixTile + 1;
     const size_t hist = align_up(nblocks * kRadixBins * sizeof(int32_t)) / sizeof(int32_t);

@@ -417,6 +417,13 @@ def test_full_size_configs(amd, idx):
     assert net.n_levels == nl_o and (lv == lv_o).all()
     if wl.planted_level is not None:
         assert (lv == wl.planted_level).all()
+    # the packed arrays, bit for bit (the large workloads take the preprocess paths that sort first)
+    perm, inv_np, level_ptr, row_ptr, col, w = expected_pack(wl, lv_o, nl_o)
+    g = net.graph
+    assert (g.perm.cpu().numpy() == perm).all() and (g.inv_perm.cpu().numpy() == inv_np).all()
+    assert (g.level_ptr_host == level_ptr).all() and (g.row_ptr.cpu().numpy() == row_ptr).all()
+    assert (g.col.cpu().numpy() == col).all() and (g.w.cpu().numpy() == w).all()
+    del perm, inv_np, col, w
     ncol = FULL_COLUMNS[idx]
     cols = np.arange(wl.B) if ncol is None else np.unique(np.linspace(0, wl.B - 1, ncol).astype(int))
     want = oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, np.ascontiguousarray(wl.X[:, cols]))
