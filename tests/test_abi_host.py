@@ -129,6 +129,30 @@ def test_argument_checks_need_no_device(lib):
     assert lib.asnn_activate_workspace_bytes(ctypes.byref(r), 64) >= 16000 * 64 // 32
 
 
+def test_schedule_choice_follows_the_cost_estimate(lib):
+    """asnn_activate_schedule is host arithmetic on the record: level launches (0) against the
+    dataflow launch (1) by the per-level estimate, one workgroup per tile (2) for tiny jobs."""
+    import paper_2005_04347_amd.binding as b
+    F = 256
+
+    def rec(n, L, e, heavy):
+        return b.AsnnPacked(n_nodes=n, n_levels=L, n_edges=e, n_units=n // 5, first_unit=10, max_heavy_indegree=heavy,
+                            level_ptr_host=None, level_ptr=F, perm=F, inv_perm=F, row_ptr=F, col=F, w=F, unit_ptr=F)
+
+    sched = lambda r, B, ws=1, flags=0: lib.asnn_activate_schedule(ctypes.byref(r), B, ws, flags)
+    wide = rec(100000, 50, 1090000, 0)              # the 100k-node workload: no heavy rows
+    assert [sched(wide, B) for B in (64, 256, 384, 1024)] == [1, 1, 0, 0]
+    assert sched(wide, 256, ws=0) == 0              # no workspace, no dataflow
+    deep = rec(1000000, 1000, 16000000, 4096)       # 1000 levels with rows of 4096 connections
+    assert [sched(deep, B) for B in (8, 64, 512, 1024)] == [1, 1, 1, 1]
+    assert sched(deep, 2048) == 0                   # the value matrix passes 4 GiB: level launches
+    flat = rec(1000000, 1000, 16000000, 0)          # the same without heavy rows: the estimates meet near 8 M per level
+    assert [sched(flat, B) for B in (64, 256, 1024)] == [1, 1, 0]
+    tiny = rec(76, 20, 512, 0)
+    assert sched(tiny, 1) == 2 and sched(tiny, 4096) == 1 and sched(tiny, 4096, ws=0) == 0
+    assert sched(wide, 256, flags=4) == 0 and sched(wide, 1024, flags=8) == 1 and sched(wide, 1024, flags=16) == 2
+
+
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     import paper_2005_04347_amd.binding as b
     monkeypatch.setattr(b, "_lib", None)
