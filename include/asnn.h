@@ -153,7 +153,7 @@ typedef struct asnn_packed {
     int32_t *col;               /* device int32[n_edges]   packed row of the connection's source */
     float *w;                   /* device float[n_edges] */
     int32_t *unit_ptr;          /* device int32[n_nodes + n_edges/512 + 2] (n_units+1 used).  Work units in
-                                   packed order, each inside one level and class: up to 8 light rows,
+                                   packed order, each inside one level and class: up to 16 light rows,
                                    one medium row, or one heavy row or one chunk of it.  A heavy row
                                    of in-degree d is cut into ceil(d/len) chunks of
                                    len = max(512, ceil(d/16)) connections, one unit per chunk.

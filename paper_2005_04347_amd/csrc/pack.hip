@@ -150,7 +150,7 @@ __global__ void gather_edges_kernel(const uint32_t *__restrict__ sorted_edge, co
 
 
 // Work units, in packed order: a heavy row gives one unit per chunk of its connections (see
-// heavy_chunks), a medium row one unit, light rows go eight to a unit; a unit never spans two
+// heavy_chunks), a medium row one unit, light rows go sixteen to a unit; a unit never spans two
 // (level, class) segments.  row_units[i] = units that START at packed row i.
 __global__ void row_units_kernel(const uint32_t *__restrict__ sorted_keys, const int32_t *__restrict__ level_ptr,
                                  const int32_t *__restrict__ packed_deg, int32_t n_nodes,

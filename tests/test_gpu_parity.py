@@ -65,7 +65,7 @@ def run_gpu(amd, wl, flags=0, poison=True, X=None, net=None):
 
 
 def expected_units(level_ptr, n_levels, row_ptr):
-    """numpy statement of the work units: light rows in groups of 8 (never across a level
+    """numpy statement of the work units: light rows in groups of 16 (never across a level
     boundary), a medium row alone, a heavy row of in-degree d in ceil(d / len) chunks of
     len = max(512, ceil(d / 16)) connections, one unit each, all naming the row."""
     starts = []
@@ -79,7 +79,7 @@ def expected_units(level_ptr, n_levels, row_ptr):
                 length = max(512, -(-d // 16))
                 starts += [r] * max(1, -(-d // length))
         else:
-            starts += list(range(level_ptr[k], level_ptr[k + 1], (1, 1, 8)[k % 3]))
+            starts += list(range(level_ptr[k], level_ptr[k + 1], (1, 1, 16)[k % 3]))
     if first_unit is None:
         first_unit = len(starts)
     return np.array(starts + [level_ptr[-1]], dtype=np.int32), first_unit
