@@ -1174,13 +1174,16 @@ int choose_schedule(const asnn_packed *packed, int32_t B, bool has_workspace, ui
 
 // Level launches against the persistent dataflow launch: a cost model per level, in
 // microseconds, fitted to measurements on MI355X (w = connections*samples of an average level).
-//   level launches: 3.5 + w / 2.0e6, plus the tail of the level's heaviest row, which one
-//     16-wave workgroup per tile walks 128 connections at a time (about 0.6 us per round);
-//   dataflow: w / 1.05e6 with the batch rounded up to whole tiles, but at least the latency of a
-//     level hand-over (2 us; 3.8 us when rows are split over workgroups).
-// Without heavy rows the two meet near 8 M connections*samples per level.
-constexpr double kLevelLaunchUs = 3.5, kLevelWorkPerUs = 2.0e6, kHeavyRoundUs = 0.6;
-constexpr double kDataflowWorkPerUs = 1.05e6, kDataflowHopUs = 2.0, kDataflowSplitHopUs = 3.8;
+//   level launches: 3.5 + w / 2.0e6 (w / 3.0e6 when the value matrix fits the L2 caches, 32 MiB:
+//     the dataflow schedule reads around them), plus the tail of the level's heaviest row, which
+//     one 16-wave workgroup per tile walks 128 connections at a time (about 0.6 us per round);
+//   dataflow: w / 1.5e6 with the batch rounded up to whole tiles, but at least the latency of a
+//     level hand-over (2 us; 3.8 us when rows are split over workgroups), plus its share of the
+//     5 us the extra launch and the start of the persistent grid cost once.
+// Without heavy rows the two meet near 20 M connections*samples per level.
+constexpr double kLevelLaunchUs = 3.5, kLevelWorkPerUs = 2.0e6, kLevelWorkPerUsCached = 3.0e6, kHeavyRoundUs = 0.6;
+constexpr double kCachedValueBytes = 32.0 * 1024.0 * 1024.0;
+constexpr double kDataflowWorkPerUs = 1.5e6, kDataflowHopUs = 2.0, kDataflowSplitHopUs = 3.8, kDataflowStartUs = 5.0;
 // Connections*samples up to which one workgroup per tile beats the schedules that spread a
 // level over the chip.  Measured on MI355X at B = 1: the workgroup schedule takes about
 // 12 us + 0.8 us per level + 0.6 ns per connection, the dataflow schedule about
@@ -1217,11 +1220,13 @@ int choose_schedule(const asnn_packed *packed, int32_t B, bool has_workspace, ui
     if (workgroup_possible && packed->n_edges * (int64_t)B <= kWorkgroupBaseWork + kWorkgroupWorkPerLevel * n_levels) return 2;
     if (!possible) return 0;
     const double per_level = (double)packed->n_edges / (double)(n_levels - 1);
-    const double levels_us = kLevelLaunchUs + per_level * (double)B / kLevelWorkPerUs +
+    const bool cached = (double)n_nodes * (double)B * 4.0 <= kCachedValueBytes;
+    const double levels_us = kLevelLaunchUs + per_level * (double)B / (cached ? kLevelWorkPerUsCached : kLevelWorkPerUs) +
                              kHeavyRoundUs * (double)(packed->max_heavy_indegree / (kMixedWaves * kUnroll));
     const double hop_us = packed->max_heavy_indegree > kHeavyChunk ? kDataflowSplitHopUs : kDataflowHopUs;
-    const double flow_us = per_level * (double)padded_batch(B) / kDataflowWorkPerUs;
-    return (flow_us > hop_us ? flow_us : hop_us) < levels_us ? 1 : 0;
+    const double stream_us = per_level * (double)padded_batch(B) / kDataflowWorkPerUs;
+    const double flow_us = (stream_us > hop_us ? stream_us : hop_us) + kDataflowStartUs / (double)(n_levels - 1);
+    return flow_us < levels_us ? 1 : 0;
 }
 }  // namespace
 }  // namespace asnn

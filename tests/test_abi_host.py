@@ -141,13 +141,15 @@ def test_schedule_choice_follows_the_cost_estimate(lib):
 
     sched = lambda r, B, ws=1, flags=0: lib.asnn_activate_schedule(ctypes.byref(r), B, ws, flags)
     wide = rec(100000, 50, 1090000, 0)              # the 100k-node workload: no heavy rows
-    assert [sched(wide, B) for B in (64, 256, 384, 1024)] == [1, 1, 0, 0]
+    assert [sched(wide, B) for B in (64, 256, 768, 1024)] == [1, 1, 1, 0]
     assert sched(wide, 256, ws=0) == 0              # no workspace, no dataflow
     deep = rec(1000000, 1000, 16000000, 4096)       # 1000 levels with rows of 4096 connections
     assert [sched(deep, B) for B in (8, 64, 512, 1024)] == [1, 1, 1, 1]
     assert sched(deep, 2048) == 0                   # the value matrix passes 4 GiB: level launches
-    flat = rec(1000000, 1000, 16000000, 0)          # the same without heavy rows: the estimates meet near 8 M per level
-    assert [sched(flat, B) for B in (64, 256, 1024)] == [1, 1, 0]
+    flat = rec(1000000, 1000, 16000000, 0)          # the same without heavy rows: the estimates meet near 20 M per level
+    assert [sched(flat, B) for B in (64, 1024, 1536)] == [1, 1, 0]
+    mlp = rec(2694, 4, 165680, 0)                   # few levels and a value matrix that fits the L2 caches
+    assert sched(mlp, 256) == 0
     tiny = rec(76, 20, 512, 0)
     assert sched(tiny, 1) == 2 and sched(tiny, 4096) == 1 and sched(tiny, 4096, ws=0) == 0
     assert sched(wide, 256, flags=4) == 0 and sched(wide, 1024, flags=8) == 1 and sched(wide, 1024, flags=16) == 2
