@@ -681,6 +681,33 @@ __device__ inline void row_sum_serial(const int32_t *__restrict__ col, const flo
     }
 }
 
+// Value of the lane SHIFT places further on in the same row of 16 lanes, wrapping round: one DPP
+// move per dword.
+template <int SHIFT>
+__device__ inline float from_lane_rotated(float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x120 + SHIFT, 0xf, 0xf, false));
+}
+template <int SHIFT>
+__device__ inline double from_lane_rotated(double x) {
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), 0x120 + SHIFT, 0xf, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), 0x120 + SHIFT, 0xf, 0xf, false);
+    return __hiloint2double(hi, lo);
+}
+
+// Sum over the lane groups of a team (16 consecutive lanes, 16/LPG groups of LPG lanes each),
+// pairwise at distances 8, 4, ... LPG.  Every group ends up with the total (each with its own
+// order of the additions: take one element from one group only).
+template <int VEC, int LPG, typename ACC>
+__device__ inline void team_sum(ACC (&acc)[VEC]) {
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) {
+        if constexpr (LPG <= 8) acc[j] += from_lane_rotated<8>(acc[j]);
+        if constexpr (LPG <= 4) acc[j] += from_lane_rotated<4>(acc[j]);
+        if constexpr (LPG <= 2) acc[j] += from_lane_rotated<2>(acc[j]);
+        if constexpr (LPG <= 1) acc[j] += from_lane_rotated<1>(acc[j]);
+    }
+}
+
 // STAGED: the packed connections and the workgroup's tile of V live in LDS for the whole
 // activation (dynamic LDS: V tile [n_nodes][T] floats, then row_ptr, col, w, level_ptr), so a level costs
 // LDS round trips instead of L2 ones; the tile is copied to V in global memory at the end.
@@ -755,6 +782,12 @@ __global__ __launch_bounds__(kMixedBlock) void workgroup_kernel(
     }
     __syncthreads();
 
+    // teams of 16 lanes for the light rows of narrow levels (see there)
+    constexpr bool kTeams = LPG <= 8;
+    constexpr int S = kTeams ? 16 / LPG : 1;                 // lane groups per team
+    constexpr int UT = 2 * LPG < 8 ? 2 * LPG : 8;            // connections per group and round
+    constexpr int kTeamRowsMost = kMixedBlock / 16;          // one row per team; beyond, the serial walk wins
+
     for (int l = 1; l < n_levels; ++l) {
         const int hb = lp[ASNN_CLASSES * l], mb = lp[ASNN_CLASSES * l + 1], lb = lp[ASNN_CLASSES * l + 2],
                   le = lp[ASNN_CLASSES * l + 3];
@@ -802,6 +835,55 @@ __global__ __launch_bounds__(kMixedBlock) void workgroup_kernel(
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) out[j] = squash(acc[j]);
                 put(row, out);
+            }
+        } else if (kTeams && le - lb <= kTeamRowsMost) {     // workgroup-uniform
+            // A level of few light rows: a lane group walking its row alone issues some 150
+            // instructions per 8 connections, one after the other.  Here a team of 16 lanes shares
+            // a row, its S groups taking every S-th connection (a light row has fewer than 32, so
+            // one round of S x UT), and the groups' sums meet through DPP moves.
+            const int sg = (lane % 16) / LPG;                 // lane group inside the team
+            for (int row = lb + (int)(threadIdx.x / 16); row < le; row += kMixedBlock / 16) {
+                const int e0 = rp[row], e1 = rp[row + 1];
+                ACC acc[VEC];
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) acc[j] = ACC(0);
+                for (int base = e0; base < e1; base += S * UT) {
+                    int cc[UT];
+                    float ww[UT];
+                    float vals[UT][VEC];
+#pragma unroll
+                    for (int k = 0; k < UT; ++k) {
+                        const int ek = min(base + k * S + sg, e1 - 1);    // padded slots re-read the last connection
+                        cc[k] = cl[ek];
+                        ww[k] = wt[ek];
+                    }
+#pragma unroll
+                    for (int k = 0; k < UT; ++k) load_vec<VEC>(Vr + (size_t)cc[k] * (size_t)ld + cr, vals[k]);
+#pragma unroll
+                    for (int k = 0; k < UT; ++k)
+#pragma unroll
+                        for (int j = 0; j < VEC; ++j) {
+                            const ACC t = acc[j] + (ACC)ww[k] * (ACC)vals[k][j];
+                            acc[j] = (base + k * S + sg < e1) ? t : acc[j];
+                        }
+                }
+                team_sum<VEC, LPG, ACC>(acc);
+                // the sigmoids of a lane's VEC columns go to different groups of the team
+#pragma unroll
+                for (int r = 0; r < (VEC + S - 1) / S; ++r) {
+                    const int jsel = sg + r * S;
+                    ACC mine = acc[0];
+#pragma unroll
+                    for (int j = 1; j < VEC; ++j) mine = (jsel == j) ? acc[j] : mine;
+                    if (jsel < VEC) {
+                        const float out = squash(mine);
+                        if constexpr (STAGED) {
+                            s_V[row * T + ct + jsel] = out;
+                        } else {
+                            if (col_ok) V[(size_t)row * (size_t)B + c + jsel] = out;
+                        }
+                    }
+                }
             }
         } else {
             for (int row = lb + slot; row < le; row += kSlots) {
