@@ -69,7 +69,8 @@ extern "C" {
  * (in-degree >= ASNN_HEAVY_INDEGREE) first, then the medium ones
  * (>= ASNN_MEDIUM_INDEGREE), then the light ones (see asnn_pack_csr): the
  * activation gives a heavy row 16 wavefronts (and, in the dataflow schedule,
- * several workgroups), a medium row 8 or 16, a light row 1. */
+ * several workgroups), a medium row 8 or 16, a light row 1 (a lane group of
+ * it, or a team of 16 lanes, in the workgroup schedule). */
 #define ASNN_HEAVY_INDEGREE 256
 #define ASNN_MEDIUM_INDEGREE 32
 #define ASNN_CLASSES 3

@@ -786,7 +786,11 @@ __global__ __launch_bounds__(kMixedBlock) void workgroup_kernel(
     constexpr bool kTeams = LPG <= 8;
     constexpr int S = kTeams ? 16 / LPG : 1;                 // lane groups per team
     constexpr int UT = 2 * LPG < 8 ? 2 * LPG : 8;            // connections per group and round
-    constexpr int kTeamRowsMost = kMixedBlock / 16;          // one row per team; beyond, the serial walk wins
+    // A pass of the teams over 64 rows takes about 0.45 us at one column per lane, a pass of the
+    // serial walk (up to 1024 rows) 0.8 us from LDS and twice that from global memory: two passes
+    // of the teams still pay.  With more columns per lane the sigmoids dominate both and the serial
+    // walk wins from the second pass on.
+    constexpr int kTeamRowsMost = (VEC == 1 ? 2 : 1) * (kMixedBlock / 16);
 
     for (int l = 1; l < n_levels; ++l) {
         const int hb = lp[ASNN_CLASSES * l], mb = lp[ASNN_CLASSES * l + 1], lb = lp[ASNN_CLASSES * l + 2],
