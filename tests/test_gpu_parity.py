@@ -145,6 +145,32 @@ def test_batch_widths_cover_every_lane_layout(amd, B):
         assert err32 <= TOL, (sched, err32)
 
 
+@pytest.mark.parametrize("rows_per_level", [25, 100])
+@pytest.mark.parametrize("B", [1, 2, 3, 4, 5, 8, 12, 16, 20, 32, 36])
+def test_narrow_levels_in_one_workgroup(amd, B, rows_per_level):
+    """The workgroup schedule hands the light rows of a narrow level to teams of 16 lanes (at most 64
+    rows, 128 with one column per lane) and walks wider levels one lane group per row: both sides of
+    that switch for every lane layout that has teams, with rows of up to 31 connections (more than
+    one round for the layouts whose teams hold few lane groups)."""
+    n_levels = 9
+    n_io = 11
+    wl = layered_skip(seed=3 + rows_per_level, n_nodes=2 * n_io + rows_per_level * (n_levels - 2), n_inputs=n_io,
+                      n_outputs=n_io, n_levels=n_levels, B=B, mean_extra_degree=15.0)
+    indeg = np.bincount(wl.dst, minlength=wl.n_nodes)
+    assert ((indeg > 16) & (indeg < 32)).sum() > 20            # light rows that need a second round
+    want = oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.X)
+    net, V, Y = run_gpu(amd, wl, flags=WORKGROUP)
+    got = net.values_original_order(V).cpu().numpy()
+    err = float(np.abs(got.astype(np.float64) - want).max())
+    assert err <= TIGHT, err
+    assert (Y.cpu().numpy() == got[wl.output_ids]).all()
+    _, V32, _ = run_gpu(amd, wl, flags=WORKGROUP | amd.FLAG_ACC_F32, net=net)
+    err32 = float(np.abs(net.values_original_order(V32).cpu().numpy().astype(np.float64) - want).max())
+    assert err32 <= TOL, err32
+    _, V2, _ = run_gpu(amd, wl, flags=WORKGROUP, net=net)
+    assert torch.equal(V, V2)                                  # the order of the additions is fixed
+
+
 @pytest.mark.parametrize("B", [1, 5, 64, 130])
 def test_output_rows_of_any_level_and_bad_ids(amd, B):
     """Y takes the rows of output_ids whatever their level: a sensor, a hidden node, a node listed
