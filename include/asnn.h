@@ -195,11 +195,13 @@ int asnn_pack_csr(const int32_t *src, const int32_t *dst, const float *w, const 
  *     launch.  Meant for small networks and narrow batches (the paper's own
  *     regime: one input vector, thousands of connections), where launches
  *     and level hand-overs cost more than the connections.
- * By default: the workgroup schedule up to n_edges*B = 13000 + 1300*n_levels; else the
- * dataflow schedule when a workspace is given and the levels are small (up to about
- * 20 M connections*samples per level; more when the network has rows with thousands
- * of connections, which a level launch has to wait for; less when the value matrix
- * fits the L2 caches); else level launches.  ASNN_FLAG_LEVEL_LAUNCHES / ASNN_FLAG_DATAFLOW /
+ * By default: the workgroup schedule up to n_edges = 13000 + 1300*n_levels at B = 1
+ * (less for wider batches: about 5500 + 190*n_levels at B = 16, 1200 + 100*n_levels
+ * at B = 64); else the dataflow schedule when a workspace is given and the levels
+ * are small (up to about 20 M connections*samples per level; more when the network
+ * has rows with thousands of connections, which a level launch has to wait for; less
+ * when the value matrix fits the L2 caches or when a level is many work units with
+ * little in each); else level launches.  ASNN_FLAG_LEVEL_LAUNCHES / ASNN_FLAG_DATAFLOW /
  * ASNN_FLAG_WORKGROUP force one (more than one of them: SIZE).
  *   packed      host record filled by asnn_pack_csr
  *   input_ids   device int32[n_inputs]  original ids; X row k feeds input_ids[k]

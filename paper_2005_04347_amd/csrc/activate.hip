@@ -62,6 +62,69 @@ __device__ inline void store_vec(float *p, const float (&in)[VEC]) {
 __device__ inline float squash(double s) { return (float)(1.0 / (1.0 + exp(-4.97 * s))); }
 __device__ inline float squash(float s) { return 1.0f / (1.0f + __expf(-4.97f * s)); }
 
+// ---- sums across the lane groups of a wavefront ---------------------------
+// Value of the lane SHIFT places further on in the same row of 16 lanes, wrapping round: one DPP
+// move per dword.
+template <int SHIFT>
+__device__ inline float from_lane_rotated(float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x120 + SHIFT, 0xf, 0xf, false));
+}
+template <int SHIFT>
+__device__ inline double from_lane_rotated(double x) {
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), 0x120 + SHIFT, 0xf, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), 0x120 + SHIFT, 0xf, 0xf, false);
+    return __hiloint2double(hi, lo);
+}
+
+// x plus the value of the same lane in the partner row (rows of 16 lanes: 0 with 1, 2 with 3), and
+// in the partner half of the wavefront: the lane-swap instructions of gfx950 hand each lane both.
+__device__ inline float plus_partner_row(float x) {
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ inline double plus_partner_row(double x) {
+    const unsigned lo = (unsigned)__double2loint(x), hi = (unsigned)__double2hiint(x);
+    const auto rl = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
+    const auto rh = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
+    return __hiloint2double((int)rh[0], (int)rl[0]) + __hiloint2double((int)rh[1], (int)rl[1]);
+}
+__device__ inline float plus_partner_half(float x) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ inline double plus_partner_half(double x) {
+    const unsigned lo = (unsigned)__double2loint(x), hi = (unsigned)__double2hiint(x);
+    const auto rl = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
+    const auto rh = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
+    return __hiloint2double((int)rh[0], (int)rl[0]) + __hiloint2double((int)rh[1], (int)rl[1]);
+}
+
+// Sum over the lane groups of a team (16 consecutive lanes, 16/LPG groups of LPG lanes each),
+// pairwise at distances 8, 4, ... LPG.  Every group ends up with the same total.
+template <int VEC, int LPG, typename ACC>
+__device__ inline void team_sum(ACC (&acc)[VEC]) {
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) {
+        if constexpr (LPG <= 8) acc[j] += from_lane_rotated<8>(acc[j]);
+        if constexpr (LPG <= 4) acc[j] += from_lane_rotated<4>(acc[j]);
+        if constexpr (LPG <= 2) acc[j] += from_lane_rotated<2>(acc[j]);
+        if constexpr (LPG <= 1) acc[j] += from_lane_rotated<1>(acc[j]);
+    }
+}
+
+// Sum over all 64/LPG lane groups of the wavefront: inside the rows of 16 lanes first, then the
+// rows pairwise, then the halves.  Every group ends up with the same total; all vector-ALU moves
+// (shuffles through the LDS crossbar cost a round trip per step).
+template <int VEC, int LPG, typename ACC>
+__device__ inline void wave_sum(ACC (&acc)[VEC]) {
+    team_sum<VEC, LPG, ACC>(acc);
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) {
+        if constexpr (LPG <= 16) acc[j] = plus_partner_row(acc[j]);
+        if constexpr (LPG <= 32) acc[j] = plus_partner_half(acc[j]);
+    }
+}
+
 // Partial weighted sum of connections [e_begin, e_end) of one row for this
 // lane's VEC batch columns starting at column c0 (a valid column, possibly
 // clamped).  LPG lanes cover one tile; the 64/LPG lane groups take
@@ -110,33 +173,31 @@ __device__ inline void row_sum(const int32_t *__restrict__ col, const float *__r
                 }
         }
     } else {
+        // UG slots per group and round: 32 connections or more per round for every G >= 4 (a
+        // medium row of a narrow batch would leave most of 8 slots per group padded).
+        constexpr int UG = G >= 16 ? 2 : (G >= 8 ? 4 : U);
         const int g = (threadIdx.x & (kWave - 1)) / LPG;
-        for (int base = e_begin; base < e_end; base += G * U) {
-            int cc[U];
-            float ww[U];
-            bool ok[U];
-            float vals[U][VEC];
+        for (int base = e_begin; base < e_end; base += G * UG) {
+            int cc[UG];
+            float ww[UG];
+            float vals[UG][VEC];
 #pragma unroll
-            for (int k = 0; k < U; ++k) {
-                const int ek = base + k * G + g;
-                ok[k] = ek < e_end;
-                cc[k] = ok[k] ? col[ek] : 0;
-                ww[k] = ok[k] ? w[ek] : 0.0f;
+            for (int k = 0; k < UG; ++k) {
+                const int ek = min(base + k * G + g, e_end - 1);      // padded slots re-read the last connection
+                cc[k] = col[ek];
+                ww[k] = w[ek];
             }
 #pragma unroll
-            for (int k = 0; k < U; ++k) load_vec<VEC>(Vc + (size_t)cc[k] * (size_t)B, vals[k]);
+            for (int k = 0; k < UG; ++k) load_vec<VEC>(Vc + (size_t)cc[k] * (size_t)B, vals[k]);
 #pragma unroll
-            for (int k = 0; k < U; ++k)
+            for (int k = 0; k < UG; ++k)
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) {
                     const ACC t = acc[j] + (ACC)ww[k] * (ACC)vals[k][j];
-                    acc[j] = ok[k] ? t : acc[j];     // a padded slot must not turn 0*inf into NaN
+                    acc[j] = (base + k * G + g < e_end) ? t : acc[j];     // a padded slot adds nothing
                 }
         }
-#pragma unroll
-        for (int off = LPG; off < kWave; off <<= 1)
-#pragma unroll
-            for (int j = 0; j < VEC; ++j) acc[j] += __shfl_xor(acc[j], off, kWave);
+        wave_sum<VEC, LPG, ACC>(acc);
     }
 }
 
@@ -450,6 +511,7 @@ __device__ inline void row_sum_dataflow(const int32_t *__restrict__ col, const f
         }
     }
     if constexpr (G > 1) {
+        // (shuffles here: the lane-swap sum measured 1.7 % slower on the deep workload)
 #pragma unroll
         for (int off = LPG; off < kWave; off <<= 1)
 #pragma unroll
@@ -678,33 +740,6 @@ __device__ inline void row_sum_serial(const int32_t *__restrict__ col, const flo
                 const ACC t = acc[j] + (ACC)ww[k] * (ACC)vals[k][j];
                 acc[j] = (e + k < e_end) ? t : acc[j];
             }
-    }
-}
-
-// Value of the lane SHIFT places further on in the same row of 16 lanes, wrapping round: one DPP
-// move per dword.
-template <int SHIFT>
-__device__ inline float from_lane_rotated(float x) {
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x120 + SHIFT, 0xf, 0xf, false));
-}
-template <int SHIFT>
-__device__ inline double from_lane_rotated(double x) {
-    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), 0x120 + SHIFT, 0xf, 0xf, false);
-    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), 0x120 + SHIFT, 0xf, 0xf, false);
-    return __hiloint2double(hi, lo);
-}
-
-// Sum over the lane groups of a team (16 consecutive lanes, 16/LPG groups of LPG lanes each),
-// pairwise at distances 8, 4, ... LPG.  Every group ends up with the total (each with its own
-// order of the additions: take one element from one group only).
-template <int VEC, int LPG, typename ACC>
-__device__ inline void team_sum(ACC (&acc)[VEC]) {
-#pragma unroll
-    for (int j = 0; j < VEC; ++j) {
-        if constexpr (LPG <= 8) acc[j] += from_lane_rotated<8>(acc[j]);
-        if constexpr (LPG <= 4) acc[j] += from_lane_rotated<4>(acc[j]);
-        if constexpr (LPG <= 2) acc[j] += from_lane_rotated<2>(acc[j]);
-        if constexpr (LPG <= 1) acc[j] += from_lane_rotated<1>(acc[j]);
     }
 }
 
@@ -1264,19 +1299,38 @@ int choose_schedule(const asnn_packed *packed, int32_t B, bool has_workspace, ui
 //     the dataflow schedule reads around them), plus the tail of the level's heaviest row, which
 //     one 16-wave workgroup per tile walks 128 connections at a time (about 0.6 us per round);
 //   dataflow: w / 1.5e6 with the batch rounded up to whole tiles, but at least the latency of a
-//     level hand-over (2 us; 3.8 us when rows are split over workgroups), plus its share of the
-//     5 us the extra launch and the start of the persistent grid cost once.
+//     level hand-over (2 us; 3.8 us when rows are split over workgroups) and at least the time the
+//     level's work items take at 5 us each on the 512 workgroups the chip holds (a pruned
+//     multilayer perceptron at a narrow batch is one item per row and tile with little in it),
+//     plus its share of the 5 us the extra launch and the start of the persistent grid cost once.
 // Without heavy rows the two meet near 20 M connections*samples per level.
 constexpr double kLevelLaunchUs = 3.5, kLevelWorkPerUs = 2.0e6, kLevelWorkPerUsCached = 3.0e6, kHeavyRoundUs = 0.6;
 constexpr double kCachedValueBytes = 32.0 * 1024.0 * 1024.0;
 constexpr double kDataflowWorkPerUs = 1.5e6, kDataflowHopUs = 2.0, kDataflowSplitHopUs = 3.8, kDataflowStartUs = 5.0;
-// Connections*samples up to which one workgroup per tile beats the schedules that spread a
-// level over the chip.  Measured on MI355X at B = 1: the workgroup schedule takes about
-// 12 us + 0.8 us per level + 0.6 ns per connection, the dataflow schedule about
-// 20 us + 1.6 us per level and next to nothing per connection, so the break-even grows
-// with the depth (20k connections at 5 levels, 66k at 40).
-constexpr int64_t kWorkgroupBaseWork = 13000;
-constexpr int64_t kWorkgroupWorkPerLevel = 1300;
+constexpr double kDataflowItemUs = 5.0, kDataflowResidentWorkgroups = 512.0;
+// Connections up to which one workgroup per tile beats the schedules that spread a level over the
+// chip: base + per_level * n_levels.  Measured on MI355X at B = 1: the workgroup schedule takes
+// about 11 us + 0.45 us per level + 0.8 ns per connection, the dataflow schedule about
+// 9 us + 1.9 us per level and next to nothing per connection, so the break-even grows with the
+// depth (20k connections at 5 levels, 65k at 40, 117k at 80).  Wider tiles leave the workgroup fewer
+// rows in flight (16 * 64/LPG lane groups) and more sigmoids per lane: break-evens read off sweeps
+// over 4k-150k connections x 5-80 levels at B = 4, 16, 64 and 256 were 13k + 400 L, 5.5k + 190 L,
+// 1.2k + 100 L and about 220 L connections, which the two factors below follow.
+constexpr double kWorkgroupBaseConnections = 13000.0;
+constexpr double kWorkgroupConnectionsPerLevel = 1300.0;          // one column per lane
+constexpr double kWorkgroupConnectionsPerLevelVec2 = 800.0;       // two
+constexpr double kWorkgroupConnectionsPerLevelVec4 = 400.0;       // four
+inline double workgroup_break_even(int B, int n_levels) {
+    const int vec = vec_for_workgroup(B);
+    const int vecs = B / vec;
+    int lpg = 1;
+    while (lpg < 64 && lpg < vecs) lpg <<= 1;
+    const double base = kWorkgroupBaseConnections / (lpg > 1 ? (double)lpg / 1.7 : 1.0);
+    const double per_level = (vec == 1 ? kWorkgroupConnectionsPerLevel
+                                       : vec == 2 ? kWorkgroupConnectionsPerLevelVec2 : kWorkgroupConnectionsPerLevelVec4) /
+                             pow((double)lpg, vec == 1 ? 0.42 : 0.5);
+    return base + per_level * (double)n_levels;
+}
 
 }  // namespace
 }  // namespace asnn
@@ -1303,7 +1357,9 @@ int choose_schedule(const asnn_packed *packed, int32_t B, bool has_workspace, ui
         return possible ? 1 : 0;
     }
     if (flags & ASNN_FLAG_LEVEL_LAUNCHES) return 0;
-    if (workgroup_possible && packed->n_edges * (int64_t)B <= kWorkgroupBaseWork + kWorkgroupWorkPerLevel * n_levels) return 2;
+    // (one workgroup per tile: beyond the 512 workgroups the chip holds they run in rounds)
+    const double workgroup_rounds = ceil((double)tiles_for_workgroup(B) / kDataflowResidentWorkgroups);
+    if (workgroup_possible && (double)packed->n_edges * workgroup_rounds <= workgroup_break_even(B, n_levels)) return 2;
     if (!possible) return 0;
     const double per_level = (double)packed->n_edges / (double)(n_levels - 1);
     const bool cached = (double)n_nodes * (double)B * 4.0 <= kCachedValueBytes;
@@ -1311,7 +1367,10 @@ int choose_schedule(const asnn_packed *packed, int32_t B, bool has_workspace, ui
                              kHeavyRoundUs * (double)(packed->max_heavy_indegree / (kMixedWaves * kUnroll));
     const double hop_us = packed->max_heavy_indegree > kHeavyChunk ? kDataflowSplitHopUs : kDataflowHopUs;
     const double stream_us = per_level * (double)padded_batch(B) / kDataflowWorkPerUs;
-    const double flow_us = (stream_us > hop_us ? stream_us : hop_us) + kDataflowStartUs / (double)(n_levels - 1);
+    const double items_us = (double)n_work / (double)(n_levels - 1) / kDataflowResidentWorkgroups * kDataflowItemUs;
+    double flow_us = stream_us > hop_us ? stream_us : hop_us;
+    if (items_us > flow_us) flow_us = items_us;
+    flow_us += kDataflowStartUs / (double)(n_levels - 1);
     return flow_us < levels_us ? 1 : 0;
 }
 }  // namespace

@@ -135,8 +135,9 @@ def test_schedule_choice_follows_the_cost_estimate(lib):
     import paper_2005_04347_amd.binding as b
     F = 256
 
-    def rec(n, L, e, heavy):
-        return b.AsnnPacked(n_nodes=n, n_levels=L, n_edges=e, n_units=n // 5, first_unit=10, max_heavy_indegree=heavy,
+    def rec(n, L, e, heavy, units=None):            # light rows go 16 to a work unit
+        return b.AsnnPacked(n_nodes=n, n_levels=L, n_edges=e, n_units=(n // 16 if units is None else units) + 10,
+                            first_unit=10, max_heavy_indegree=heavy,
                             level_ptr_host=None, level_ptr=F, perm=F, inv_perm=F, row_ptr=F, col=F, w=F, unit_ptr=F)
 
     sched = lambda r, B, ws=1, flags=0: lib.asnn_activate_schedule(ctypes.byref(r), B, ws, flags)
@@ -148,10 +149,18 @@ def test_schedule_choice_follows_the_cost_estimate(lib):
     assert sched(deep, 2048) == 0                   # the value matrix passes 4 GiB: level launches
     flat = rec(1000000, 1000, 16000000, 0)          # the same without heavy rows: the estimates meet near 20 M per level
     assert [sched(flat, B) for B in (64, 1024, 1536)] == [1, 1, 0]
-    mlp = rec(2694, 4, 165680, 0)                   # few levels and a value matrix that fits the L2 caches
-    assert sched(mlp, 256) == 0
+    mlp = rec(2694, 4, 165680, 0, units=1910)       # few levels, a value matrix that fits the L2 caches, and
+    assert [sched(mlp, B) for B in (16, 64, 256)] == [0, 0, 0]      # a work item per medium row with little in it
+    assert sched(rec(400, 10, 17600, 0, units=380), 16) == 1        # the same rows, 40 to a level: dataflow
     tiny = rec(76, 20, 512, 0)
-    assert sched(tiny, 1) == 2 and sched(tiny, 4096) == 1 and sched(tiny, 4096, ws=0) == 0
+    assert sched(tiny, 1) == 2 and sched(tiny, 4096) == 2 and sched(tiny, 4096, ws=0) == 2
+    assert sched(tiny, 1 << 20) == 0 and sched(tiny, 1 << 20, ws=0) == 0      # more tiles than the chip holds workgroups
+    # the break-even of one workgroup per tile shrinks as the tile widens (fewer rows in flight)
+    small = lambda e, L: rec(e // 10, L, e, 0)
+    assert [sched(small(16000, 5), B) for B in (1, 4, 16)] == [2, 1, 1]
+    assert [sched(small(4000, 20), B) for B in (1, 16, 64)] == [2, 2, 1]
+    assert [sched(small(8000, 40), B) for B in (16, 64, 256)] == [2, 1, 2]
+    assert [sched(small(70000, 80), B) for B in (1, 4)] == [2, 1]
     assert sched(wide, 256, flags=4) == 0 and sched(wide, 1024, flags=8) == 1 and sched(wide, 1024, flags=16) == 2
 
 

@@ -559,7 +559,8 @@ def test_schedule_choice_is_reported(amd):
     tnet = amd.Network(tiny.n_nodes, tiny.src, tiny.dst, tiny.w, tiny.input_ids, tiny.output_ids)
     assert amd.asnn_activate_schedule(tnet.graph, 1, True, 0) == "workgroup"
     assert amd.asnn_activate_schedule(tnet.graph, 8, False, 0) == "workgroup"
-    assert amd.asnn_activate_schedule(tnet.graph, 4096, False, 0) == "levels"       # wide batch: spread over the chip
+    assert amd.asnn_activate_schedule(tnet.graph, 4096, False, 0) == "workgroup"    # 64 tiles, a workgroup each
+    assert amd.asnn_activate_schedule(tnet.graph, 1 << 20, False, 0) == "levels"    # more tiles than the chip holds workgroups
 
 
 @pytest.mark.parametrize("idx,scale", [(1, "small"), (3, "small"), (4, "small"), (5, "small"), (3, "full")])
