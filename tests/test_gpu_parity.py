@@ -171,6 +171,25 @@ def test_narrow_levels_in_one_workgroup(amd, B, rows_per_level):
     assert torch.equal(V, V2)                                  # the order of the additions is fixed
 
 
+@pytest.mark.parametrize("B", [1, 3, 8, 32])
+def test_narrow_levels_of_a_network_too_large_for_lds(amd, B):
+    """The same teams when the workgroup schedule reads the network from global memory (some
+    60 000 connections: beyond what a workgroup can stage) and stores each value straight to V."""
+    n_levels, n_io, rows_per_level = 150, 9, 30
+    wl = layered_skip(seed=11, n_nodes=2 * n_io + rows_per_level * (n_levels - 2), n_inputs=n_io, n_outputs=n_io,
+                      n_levels=n_levels, B=B, mean_extra_degree=12.5)
+    assert wl.n_edges * 8 > 160 * 1024
+    want = oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.X)
+    net, V, Y = run_gpu(amd, wl, flags=WORKGROUP)
+    got = net.values_original_order(V).cpu().numpy()
+    err = float(np.abs(got.astype(np.float64) - want).max())
+    assert err <= TIGHT, err
+    assert (Y.cpu().numpy() == got[wl.output_ids]).all()
+    _, V32, _ = run_gpu(amd, wl, flags=WORKGROUP | amd.FLAG_ACC_F32, net=net)
+    err32 = float(np.abs(net.values_original_order(V32).cpu().numpy().astype(np.float64) - want).max())
+    assert err32 <= 30 * TOL, err32
+
+
 @pytest.mark.parametrize("B", [1, 5, 64, 130])
 def test_output_rows_of_any_level_and_bad_ids(amd, B):
     """Y takes the rows of output_ids whatever their level: a sensor, a hidden node, a node listed
