@@ -69,7 +69,7 @@ extern "C" {
  * (in-degree >= ASNN_HEAVY_INDEGREE) first, then the medium ones
  * (>= ASNN_MEDIUM_INDEGREE), then the light ones (see asnn_pack_csr): the
  * activation gives a heavy row 16 wavefronts (and, in the dataflow schedule,
- * several workgroups), a medium row 8 or 16, a light row 1 (a lane group of
+ * several workgroups), a medium row 4, 8 or 16, a light row 1 (a lane group of
  * it, or a team of 16 lanes, in the workgroup schedule). */
 #define ASNN_HEAVY_INDEGREE 256
 #define ASNN_MEDIUM_INDEGREE 32
@@ -155,7 +155,8 @@ typedef struct asnn_packed {
     float *w;                   /* device float[n_edges] */
     int32_t *unit_ptr;          /* device int32[n_nodes + n_edges/512 + 2] (n_units+1 used).  Work units in
                                    packed order, each inside one level and class: up to 16 light rows,
-                                   one medium row, or one heavy row or one chunk of it.  A heavy row
+                                   one medium row (up to 4 in a level that has 256 or more of
+                                   them), or one heavy row or one chunk of it.  A heavy row
                                    of in-degree d is cut into ceil(d/len) chunks of
                                    len = max(512, ceil(d/16)) connections, one unit per chunk.
                                    unit_ptr[u] = first packed row of unit u (the chunks of one row

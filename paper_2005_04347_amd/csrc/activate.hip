@@ -595,7 +595,8 @@ __global__ __launch_bounds__(kMixedBlock) void dataflow_kernel(const int32_t *__
         const int row0_begin = row_ptr[r0], row0_end = row_ptr[r0 + 1];
         const int d0 = row0_end - row0_begin;
         const bool heavy = d0 >= ASNN_HEAVY_INDEGREE;
-        const int share = d0 >= ASNN_MEDIUM_INDEGREE ? kMixedWaves : 1;     // wavefronts on one row
+        // wavefronts on one row: 16 on a heavy row, 16, 8 or 4 on the 1, 2 or 3-4 medium rows of a unit, 1 on a light row
+        const int share = d0 < ASNN_MEDIUM_INDEGREE ? 1 : (heavy || r1 - r0 == 1) ? kMixedWaves : (r1 - r0 == 2 ? 8 : 4);
         // A heavy row may be cut into chunks, one unit each (consecutive units that name the same row).
         const int n_chunks = heavy ? heavy_chunks(d0) : 1;
         int chunk = 0;
@@ -624,7 +625,7 @@ __global__ __launch_bounds__(kMixedBlock) void dataflow_kernel(const int32_t *__
 #pragma unroll
             for (int j = 0; j < VEC; ++j) acc[j] = ACC(0);
         }
-        if (share > 1) {                               // block-uniform: a heavy or medium row, `row` is r0
+        if (share > 1) {                               // block-uniform: a heavy row (`row` is r0) or medium rows
             // The wavefronts' partial sums meet in LDS.  From here on the tile is spread over all
             // lanes of wavefront 0 (E elements per lane), so that the additions, the sigmoid and the
             // store that follow the last gathered source take as few instructions as possible.
@@ -655,13 +656,18 @@ __global__ __launch_bounds__(kMixedBlock) void dataflow_kernel(const int32_t *__
                 for (int j = 0; j < E; ++j) others[wave][el + j] = p[j];
             }
             __syncthreads();
-            if (wave == 0 && lane < EL) {
+            if (slice == 0 && valid && lane < EL) {         // the first wavefront of every row
                 ACC sum[E];
 #pragma unroll
                 for (int j = 0; j < E; ++j) {
                     ACC t = ACC(0);
+                    if (share == kMixedWaves) {
 #pragma unroll
-                    for (int k = 0; k < kMixedWaves; ++k) t += part[k][el + j];
+                        for (int k = 0; k < kMixedWaves; ++k) t += part[k][el + j];
+                    } else {                            // grouped medium rows: not what a level waits for
+#pragma unroll 1
+                        for (int k = 0; k < share; ++k) t += part[wave + k][el + j];
+                    }
                     sum[j] = t;
                 }
                 if (split && !last_chunk) {

@@ -37,13 +37,18 @@ inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 // with thousands of connections is gathered by several compute units at once instead of round
 // after round by one: at most kMaxHeavyChunks chunks of at least kHeavyChunk connections (512
 // is one gather round of a workgroup at 64 batch columns; 256 and 1024 both measured slower).
-// A medium row is a unit of its own (all 16 wavefronts on it), light rows go kLightUnitRows to
-// a unit, one wavefront each: sixteen fill the workgroup (eight measured faster only as long as the
-// polling loop serialised its reloads; now sixteen win at every batch width, by 2 % at 64
-// columns and 12 % at 1024).
+// A medium row is a unit of its own (all 16 wavefronts on it) in levels of fewer than
+// kMediumGroupFrom medium rows; in wider levels they go kMediumUnitRows to a unit, 4 wavefronts each
+// (a pruned multilayer perceptron is a thousand medium rows per level: as one-row units they take the
+// chip's 512 workgroups several rounds with little in each, 35-47 us against 21-25 us at batch widths up to
+// 64; a level of 40 such rows runs 15-30 % slower grouped, its rows being what the next level waits for).
+// Light rows go kLightUnitRows to a unit, one wavefront each: sixteen fill the workgroup (eight
+// measured faster only as long as the polling loop serialised its reloads; now sixteen win at every
+// batch width, by 2 % at 64 columns and 12 % at 1024).
 constexpr int kHeavyChunk = 512;
 constexpr int kMaxHeavyChunks = 16;
-constexpr int kMediumUnitRows = 1;
+constexpr int kMediumUnitRows = 4;
+constexpr int kMediumGroupFrom = 256;
 constexpr int kLightUnitRows = 16;
 __host__ __device__ inline int heavy_chunk_len(int d) {
     const int spread = (d + kMaxHeavyChunks - 1) / kMaxHeavyChunks;

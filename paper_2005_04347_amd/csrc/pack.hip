@@ -150,8 +150,8 @@ __global__ void gather_edges_kernel(const uint32_t *__restrict__ sorted_edge, co
 
 
 // Work units, in packed order: a heavy row gives one unit per chunk of its connections (see
-// heavy_chunks), a medium row one unit, light rows go sixteen to a unit; a unit never spans two
-// (level, class) segments.  row_units[i] = units that START at packed row i.
+// heavy_chunks), medium rows go one or four to a unit (by how many the level has), light rows
+// sixteen; a unit never spans two (level, class) segments.  row_units[i] = units that START at packed row i.
 __global__ void row_units_kernel(const uint32_t *__restrict__ sorted_keys, const int32_t *__restrict__ level_ptr,
                                  const int32_t *__restrict__ packed_deg, int32_t n_nodes,
                                  int32_t *__restrict__ row_units, int32_t *__restrict__ max_indegree) {
@@ -164,7 +164,10 @@ __global__ void row_units_kernel(const uint32_t *__restrict__ sorted_keys, const
     int units;
     if (cls == 0) atomicMax(max_indegree, packed_deg[i]);      // lighter rows cannot hold the maximum if a heavy one exists
     if (cls == 0) units = heavy_chunks(packed_deg[i]);
-    else if (cls == 1) units = (off % kMediumUnitRows == 0) ? 1 : 0;
+    else if (cls == 1) {
+        const int group = level_ptr[k + 1] - level_ptr[k] >= kMediumGroupFrom ? kMediumUnitRows : 1;
+        units = (off % group == 0) ? 1 : 0;
+    }
     else units = (off % kLightUnitRows == 0) ? 1 : 0;
     row_units[i] = units;
 }

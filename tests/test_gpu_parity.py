@@ -66,7 +66,7 @@ def run_gpu(amd, wl, flags=0, poison=True, X=None, net=None):
 
 def expected_units(level_ptr, n_levels, row_ptr):
     """numpy statement of the work units: light rows in groups of 16 (never across a level
-    boundary), a medium row alone, a heavy row of in-degree d in ceil(d / len) chunks of
+    boundary), medium rows alone or, in levels of 256 or more of them, in groups of 4, a heavy row of in-degree d in ceil(d / len) chunks of
     len = max(512, ceil(d / 16)) connections, one unit each, all naming the row."""
     starts = []
     first_unit = None
@@ -79,7 +79,8 @@ def expected_units(level_ptr, n_levels, row_ptr):
                 length = max(512, -(-d // 16))
                 starts += [r] * max(1, -(-d // length))
         else:
-            starts += list(range(level_ptr[k], level_ptr[k + 1], (1, 1, 16)[k % 3]))
+            step = 16 if k % 3 == 2 else (4 if level_ptr[k + 1] - level_ptr[k] >= 256 else 1)
+            starts += list(range(level_ptr[k], level_ptr[k + 1], step))
     if first_unit is None:
         first_unit = len(starts)
     return np.array(starts + [level_ptr[-1]], dtype=np.int32), first_unit
@@ -188,6 +189,33 @@ def test_narrow_levels_of_a_network_too_large_for_lds(amd, B):
     _, V32, _ = run_gpu(amd, wl, flags=WORKGROUP | amd.FLAG_ACC_F32, net=net)
     err32 = float(np.abs(net.values_original_order(V32).cpu().numpy().astype(np.float64) - want).max())
     assert err32 <= 30 * TOL, err32
+
+
+@pytest.mark.parametrize("B", [1, 16, 130])
+def test_levels_of_many_medium_rows(amd, B):
+    """Levels of 256 or more medium rows put them four to a work unit (four wavefronts a row), with
+    ragged last units of one, two and three rows; narrower levels keep a unit per row."""
+    n_io, n_levels = 40, 8
+    sizes = [300, 301, 302, 303, 120, 299]
+    wl = layered_skip(seed=21, n_nodes=2 * n_io + sum(sizes), n_inputs=n_io, n_outputs=n_io, n_levels=n_levels, B=B,
+                      mean_extra_degree=50.0)
+    want = oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.X)
+    net = amd.Network(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.output_ids)
+    g = net.graph
+    level_ptr = g.level_ptr.cpu().numpy()
+    row_ptr = g.row_ptr.cpu().numpy()
+    medium = level_ptr[2::3][:n_levels] - level_ptr[1::3][:n_levels]
+    assert (medium >= 256).sum() >= 3 and ((medium > 0) & (medium < 256)).sum() >= 1
+    assert len({int(m) % 4 for m in medium if m >= 256}) >= 2          # ragged last units
+    units, first_unit = expected_units(level_ptr, net.n_levels, row_ptr)
+    assert g.n_units == len(units) - 1 and g.first_unit == first_unit
+    assert (g.unit_ptr.cpu().numpy()[: g.n_units + 1] == units).all()
+    for sched in SCHEDULES:
+        _, V, Y = run_gpu(amd, wl, flags=sched, net=net)
+        got = net.values_original_order(V).cpu().numpy()
+        err = float(np.abs(got.astype(np.float64) - want).max())
+        assert err <= TIGHT, (sched, err)
+        assert (Y.cpu().numpy() == got[wl.output_ids]).all(), sched
 
 
 @pytest.mark.parametrize("B", [1, 5, 64, 130])
