@@ -208,7 +208,12 @@ int asnn_pack_csr(const int32_t *src, const int32_t *dst, const float *w, const 
  *   input_ids   device int32[n_inputs]  original ids; X row k feeds input_ids[k]
  *               (the ids given to asnn_build_levels)
  *   output_ids  device int32[n_outputs] original ids (may be NULL if Y is NULL)
- *   X           device float[n_inputs*B]
+ *   X           device float[n_inputs*B].  X and Y are only read and written by kernels
+ *               (plain loads and stores, each element once), so pinned host memory
+ *               that the device can address serves as well: a caller whose inputs
+ *               arrive on the host and whose outputs are wanted there saves both
+ *               copies (at one input vector an activation with the two copies takes
+ *               about 45 us, with X and Y in pinned memory about half of that)
  *   V           device float[n_nodes*B]  receives the activation of EVERY node, packed
  *               row order (row i = node perm[i]); 16-byte aligned
  *   Y           device float[n_outputs*B] or NULL; receives the rows of output_ids

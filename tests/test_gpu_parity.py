@@ -218,6 +218,24 @@ def test_levels_of_many_medium_rows(amd, B):
         assert (Y.cpu().numpy() == got[wl.output_ids]).all(), sched
 
 
+@pytest.mark.parametrize("B", [1, 130])
+def test_inputs_and_outputs_in_pinned_host_memory(amd, B):
+    """X and Y may live in pinned host memory that the device addresses: every schedule reads the
+    inputs and writes the output rows in place, with the bits of the device-resident call."""
+    wl = layered_skip(seed=9, n_nodes=500, n_inputs=17, n_outputs=13, n_levels=9, B=B, mean_extra_degree=9.0)
+    net = amd.Network(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.output_ids)
+    Xp = torch.empty(wl.X.shape, dtype=torch.float32, pin_memory=True)
+    Xp.copy_(torch.from_numpy(wl.X))
+    for sched in SCHEDULES:
+        _, V, Y = run_gpu(amd, wl, flags=sched, net=net)
+        Yp = torch.full((len(wl.output_ids), B), float("nan"), dtype=torch.float32).pin_memory()
+        V2 = torch.full((wl.n_nodes, B), float("nan"), device="cuda:0")
+        amd.asnn_activate(net.graph, net.input_ids, Xp, net.output_ids, V=V2, Y=Yp, flags=sched, workspace=net.workspace(B))
+        net.check(B)
+        assert torch.equal(V2, V), sched
+        assert torch.equal(Yp, Y.cpu()), sched
+
+
 @pytest.mark.parametrize("B", [1, 5, 64, 130])
 def test_output_rows_of_any_level_and_bad_ids(amd, B):
     """Y takes the rows of output_ids whatever their level: a sensor, a hidden node, a node listed
