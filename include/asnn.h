@@ -196,7 +196,7 @@ int asnn_pack_csr(const int32_t *src, const int32_t *dst, const float *w, const 
  *     launch.  Meant for small networks and narrow batches (the paper's own
  *     regime: one input vector, thousands of connections), where launches
  *     and level hand-overs cost more than the connections.
- * By default: the workgroup schedule up to n_edges = 13000 + 1300*n_levels at B = 1
+ * By default: the workgroup schedule up to n_edges = 13000 + 1500*n_levels at B = 1
  * (less for wider batches: about 5500 + 190*n_levels at B = 16, 1200 + 100*n_levels
  * at B = 64); else the dataflow schedule when a workspace is given and the levels
  * are small (up to about 20 M connections*samples per level; more when the network

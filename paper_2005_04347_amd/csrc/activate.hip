@@ -749,10 +749,12 @@ __device__ inline void row_sum_serial(const int32_t *__restrict__ col, const flo
     }
 }
 
-// STAGED: the packed connections and the workgroup's tile of V live in LDS for the whole
+// STAGED = 2: the packed connections and the workgroup's tile of V live in LDS for the whole
 // activation (dynamic LDS: V tile [n_nodes][T] floats, then row_ptr, col, w, level_ptr), so a level costs
 // LDS round trips instead of L2 ones; the tile is copied to V in global memory at the end.
-template <int VEC, int LPG, typename ACC, int U, bool STAGED>
+// STAGED = 1: only the tile of V does (a network too large for LDS whose values still fit): the
+// loads that depend on the level below are the LDS ones.  STAGED = 0: everything in global memory.
+template <int VEC, int LPG, typename ACC, int U, int STAGED>
 __global__ __launch_bounds__(kMixedBlock) void workgroup_kernel(
     const int32_t *__restrict__ level_ptr, int n_levels, const int32_t *__restrict__ row_ptr,
     const int32_t *__restrict__ col, const float *__restrict__ w, float *V, int B,
@@ -778,14 +780,14 @@ __global__ __launch_bounds__(kMixedBlock) void workgroup_kernel(
     int32_t *s_col = s_row_ptr + (n_nodes + 1);
     float *s_w = reinterpret_cast<float *>(s_col + n_edges);
     int32_t *s_level_ptr = reinterpret_cast<int32_t *>(s_w + n_edges);
-    const int32_t *lp = STAGED ? s_level_ptr : level_ptr;
-    const int32_t *rp = STAGED ? s_row_ptr : row_ptr;
-    const int32_t *cl = STAGED ? s_col : col;
-    const float *wt = STAGED ? s_w : w;
+    const int32_t *lp = STAGED == 2 ? s_level_ptr : level_ptr;
+    const int32_t *rp = STAGED == 2 ? s_row_ptr : row_ptr;
+    const int32_t *cl = STAGED == 2 ? s_col : col;
+    const float *wt = STAGED == 2 ? s_w : w;
     const float *Vr = STAGED ? s_V : V;
     const int ld = STAGED ? T : B;                     // row stride of Vr
     const int cr = STAGED ? ct : (col_ok ? c : 0);     // this lane's first column in Vr
-    if constexpr (STAGED) {
+    if constexpr (STAGED == 2) {
         for (int i = threadIdx.x; i <= n_nodes; i += kMixedBlock) s_row_ptr[i] = row_ptr[i];
         for (int i = threadIdx.x; i < n_edges; i += kMixedBlock) { s_col[i] = col[i]; s_w[i] = w[i]; }
         for (int i = threadIdx.x; i <= ASNN_CLASSES * n_levels; i += kMixedBlock) s_level_ptr[i] = level_ptr[i];
@@ -1215,17 +1217,24 @@ int launch_workgroup(const LevelArgs &a, const WorkgroupArgs &g) {
             most = (size_t)optin;
         budget = kLdsDefaultPerWorkgroup - fixed;
         if (most > kLdsDefaultPerWorkgroup &&
-            hipFuncSetAttribute(reinterpret_cast<const void *>(&workgroup_kernel<VEC, LPG, ACC, kUnroll, true>),
+            hipFuncSetAttribute(reinterpret_cast<const void *>(&workgroup_kernel<VEC, LPG, ACC, kUnroll, 2>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)(most - fixed)) == hipSuccess &&
+            hipFuncSetAttribute(reinterpret_cast<const void *>(&workgroup_kernel<VEC, LPG, ACC, kUnroll, 1>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)(most - fixed)) == hipSuccess)
             budget = most - fixed;
         (void)hipGetLastError();
     }
+    const size_t lds_values = ((size_t)g.n_nodes * (size_t)(LPG * VEC) * 4 + 15) & ~(size_t)15;      // the value tile alone
     if (lds <= budget) {
-        hipLaunchKernelGGL((workgroup_kernel<VEC, LPG, ACC, kUnroll, true>), dim3((unsigned)tiles), dim3(kMixedBlock), lds,
+        hipLaunchKernelGGL((workgroup_kernel<VEC, LPG, ACC, kUnroll, 2>), dim3((unsigned)tiles), dim3(kMixedBlock), lds,
+                           a.s, g.level_ptr, g.n_levels, a.row_ptr, a.col, a.w, a.V, a.B, g.input_ids, g.inv_perm, g.X,
+                           g.n_inputs, g.raw, g.output_ids, g.Y, g.n_outputs, g.n_nodes, (int)g.n_edges);
+    } else if (lds_values <= budget) {
+        hipLaunchKernelGGL((workgroup_kernel<VEC, LPG, ACC, kUnroll, 1>), dim3((unsigned)tiles), dim3(kMixedBlock), lds_values,
                            a.s, g.level_ptr, g.n_levels, a.row_ptr, a.col, a.w, a.V, a.B, g.input_ids, g.inv_perm, g.X,
                            g.n_inputs, g.raw, g.output_ids, g.Y, g.n_outputs, g.n_nodes, (int)g.n_edges);
     } else {
-        hipLaunchKernelGGL((workgroup_kernel<VEC, LPG, ACC, kUnroll, false>), dim3((unsigned)tiles), dim3(kMixedBlock), 0,
+        hipLaunchKernelGGL((workgroup_kernel<VEC, LPG, ACC, kUnroll, 0>), dim3((unsigned)tiles), dim3(kMixedBlock), 0,
                            a.s, g.level_ptr, g.n_levels, a.row_ptr, a.col, a.w, a.V, a.B, g.input_ids, g.inv_perm, g.X,
                            g.n_inputs, g.raw, g.output_ids, g.Y, g.n_outputs, g.n_nodes, (int)g.n_edges);
     }
@@ -1316,14 +1325,15 @@ constexpr double kDataflowWorkPerUs = 1.5e6, kDataflowHopUs = 2.0, kDataflowSpli
 constexpr double kDataflowItemUs = 5.0, kDataflowResidentWorkgroups = 512.0;
 // Connections up to which one workgroup per tile beats the schedules that spread a level over the
 // chip: base + per_level * n_levels.  Measured on MI355X at B = 1: the workgroup schedule takes
-// about 11 us + 0.45 us per level + 0.8 ns per connection, the dataflow schedule about
-// 9 us + 1.9 us per level and next to nothing per connection, so the break-even grows with the
-// depth (20k connections at 5 levels, 65k at 40, 117k at 80).  Wider tiles leave the workgroup fewer
-// rows in flight (16 * 64/LPG lane groups) and more sigmoids per lane: break-evens read off sweeps
-// over 4k-150k connections x 5-80 levels at B = 4, 16, 64 and 256 were 13k + 400 L, 5.5k + 190 L,
-// 1.2k + 100 L and about 220 L connections, which the two factors below follow.
+// about 11 us + 0.45 us per level + 0.6 ns per connection (next to nothing per connection while
+// the network fits in LDS), the dataflow schedule about 9 us + 1.9 us per level and next to
+// nothing per connection, so the break-even grows with the depth (20k connections at 5 levels,
+// 70k at 40, 130k at 80).  Wider tiles leave the workgroup fewer rows in flight (16 * 64/LPG
+// lane groups) and more sigmoids per lane: break-evens read off sweeps over 4k-150k connections
+// x 5-80 levels at B = 4, 16, 64 and 256 were 13k + 400 L, 5.5k + 190 L, 1.2k + 100 L and about
+// 220 L connections, which the two factors below follow.
 constexpr double kWorkgroupBaseConnections = 13000.0;
-constexpr double kWorkgroupConnectionsPerLevel = 1300.0;          // one column per lane
+constexpr double kWorkgroupConnectionsPerLevel = 1500.0;          // one column per lane
 constexpr double kWorkgroupConnectionsPerLevelVec2 = 800.0;       // two
 constexpr double kWorkgroupConnectionsPerLevelVec4 = 400.0;       // four
 inline double workgroup_break_even(int B, int n_levels) {
