@@ -466,14 +466,17 @@ __device__ inline void row_sum_dataflow(const int32_t *__restrict__ col, const f
                     }
             }
         } else {
+            // UD slots per lane group and round: with many groups (a narrow batch) one, two or four
+            // cover the 64 connections of a pass; more would be padding that is loaded and looked at all the same.
+            constexpr int UD = kWave / G < U ? kWave / G : U;
             const int g = lane / LPG;
-            for (int i = 0; i < n; i += G * U) {
-                float vals[U][VEC];
-                float ww[U];
-                uint32_t off[U];
-                bool ok[U], watch[U];   // per lane group
+            for (int i = 0; i < n; i += G * UD) {
+                float vals[UD][VEC];
+                float ww[UD];
+                uint32_t off[UD];
+                bool ok[UD], watch[UD];   // per lane group
 #pragma unroll
-                for (int k = 0; k < U; ++k) {
+                for (int k = 0; k < UD; ++k) {
                     const int idx = i + k * G + g;
                     ok[k] = idx < n;
                     const int sel = min(idx, n - 1);
@@ -487,21 +490,21 @@ __device__ inline void row_sum_dataflow(const int32_t *__restrict__ col, const f
                 // tiles that are still missing are requested again back to back: measured 6 % faster on the
                 // deep workload than looking at a slot and requesting it again one slot at a time.
                 for (;;) {
-                    bool again[U];
+                    bool again[UD];
                     bool mine = false;
 #pragma unroll
-                    for (int k = 0; k < U; ++k) {
+                    for (int k = 0; k < UD; ++k) {
                         again[k] = watch[k] && shows_not_ready<VEC>(vals[k]);
                         mine = mine || again[k];
                     }
                     if (!__any(mine)) break;
 #pragma unroll
-                    for (int k = 0; k < U; ++k)
+                    for (int k = 0; k < UD; ++k)
                         if (again[k]) load_vec_device_scope<VEC>(vres, off[k], vals[k]);
                     if (!patience.again(ctl)) break;
                 }
 #pragma unroll
-                for (int k = 0; k < U; ++k)
+                for (int k = 0; k < UD; ++k)
 #pragma unroll
                     for (int j = 0; j < VEC; ++j) {
                         const ACC t = acc[j] + (ACC)ww[k] * (ACC)vals[k][j];
@@ -510,8 +513,10 @@ __device__ inline void row_sum_dataflow(const int32_t *__restrict__ col, const f
             }
         }
     }
-    if constexpr (G > 1) {
-        // (shuffles here: the lane-swap sum measured 1.7 % slower on the deep workload)
+    if constexpr (G >= 16) {
+        wave_sum<VEC, LPG, ACC>(acc);
+    } else if constexpr (G > 1) {
+        // (up to three steps: shuffles; the lane-swap sum measured 1.7 % slower on the deep workload, two steps)
 #pragma unroll
         for (int off = LPG; off < kWave; off <<= 1)
 #pragma unroll
