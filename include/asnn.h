@@ -197,7 +197,7 @@ int asnn_pack_csr(const int32_t *src, const int32_t *dst, const float *w, const 
  *     regime: one input vector, thousands of connections), where launches
  *     and level hand-overs cost more than the connections.
  * By default: the workgroup schedule up to n_edges = 13000 + 1500*n_levels at B = 1
- * (less for wider batches: about 5500 + 190*n_levels at B = 16, 1200 + 100*n_levels
+ * (less for wider batches: about 2800 + 130*n_levels at B = 16, 700 + 45*n_levels
  * at B = 64); else the dataflow schedule when a workspace is given and the levels
  * are small (up to about 20 M connections*samples per level; more when the network
  * has rows with thousands of connections, which a level launch has to wait for; less

@@ -700,6 +700,18 @@ __global__ __launch_bounds__(kMixedBlock) void dataflow_kernel(const int32_t *__
                     }
                 }
             }
+        } else if constexpr (kWave / LPG >= VEC && VEC > 1) {
+            // light rows, one wavefront each, of a batch narrow enough for VEC lane groups or more: every
+            // group holds the sums, so group j finishes column j of its lanes' VEC columns (one sigmoid per
+            // lane instead of VEC in a row; a reader takes a tile as written once all its columns are).
+            const int gsel = lane / LPG;
+            if (active && gsel < VEC) {
+                ACC mine = acc[0];
+#pragma unroll
+                for (int j = 1; j < VEC; ++j) mine = (gsel == j) ? acc[j] : mine;
+                const float out[1] = {squash(mine)};
+                store_vec_device_scope<1>(vres, ((uint32_t)row * (uint32_t)B + (uint32_t)(c + gsel)) * 4u, out);
+            }
         } else if (active && lane < LPG) {               // light rows: one wavefront each
             float out[VEC];
 #pragma unroll
@@ -1335,8 +1347,8 @@ constexpr double kDataflowItemUs = 5.0, kDataflowResidentWorkgroups = 512.0;
 // nothing per connection, so the break-even grows with the depth (20k connections at 5 levels,
 // 70k at 40, 130k at 80).  Wider tiles leave the workgroup fewer rows in flight (16 * 64/LPG
 // lane groups) and more sigmoids per lane: break-evens read off sweeps over 4k-150k connections
-// x 5-80 levels at B = 4, 16, 64 and 256 were 13k + 400 L, 5.5k + 190 L, 1.2k + 100 L and about
-// 220 L connections, which the two factors below follow.
+// x 5-80 levels at B = 4, 16, 64 and 256 were about 6.5k + 400 L, 2.8k + 130 L, 0.7k + 45 L and
+// 220 L connections, which the factors below follow.
 constexpr double kWorkgroupBaseConnections = 13000.0;
 constexpr double kWorkgroupConnectionsPerLevel = 1500.0;          // one column per lane
 constexpr double kWorkgroupConnectionsPerLevelVec2 = 800.0;       // two
@@ -1346,10 +1358,11 @@ inline double workgroup_break_even(int B, int n_levels) {
     const int vecs = B / vec;
     int lpg = 1;
     while (lpg < 64 && lpg < vecs) lpg <<= 1;
-    const double base = kWorkgroupBaseConnections / (lpg > 1 ? (double)lpg / 1.7 : 1.0);
+    const double base = kWorkgroupBaseConnections * (vec == 4 ? 0.5 : vec == 2 ? 0.75 : 1.0) /
+                        (lpg > 1 ? (double)lpg / 1.7 : 1.0);
     const double per_level = (vec == 1 ? kWorkgroupConnectionsPerLevel
                                        : vec == 2 ? kWorkgroupConnectionsPerLevelVec2 : kWorkgroupConnectionsPerLevelVec4) /
-                             pow((double)lpg, vec == 1 ? 0.42 : 0.5);
+                             pow((double)lpg, vec == 1 ? 0.42 : 0.8);
     return base + per_level * (double)n_levels;
 }
 
