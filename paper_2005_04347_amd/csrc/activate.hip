@@ -820,6 +820,19 @@ __global__ __launch_bounds__(kMixedBlock) void workgroup_kernel(
         }
     };
 
+    // One column of a lane's VEC: lane group `gsel` of a wavefront all of whose groups hold the row's sums
+    // finishes column gsel (one sigmoid per lane instead of VEC in a row in the first group alone).
+    constexpr bool kSpread = G >= VEC && VEC > 1;
+    const int gsel = lane / LPG;
+    auto put_column = [&](int row, ACC sum) {             // column gsel of this lane's VEC
+        const float out = squash(sum);
+        if constexpr (STAGED) {
+            s_V[row * T + ct + gsel] = out;
+        } else {
+            if (col_ok) V[(size_t)row * (size_t)B + c + gsel] = out;
+        }
+    };
+
     // Level 0 has no connections: sigmoid(0), then the sensors take their inputs.
     const int level0_end = lp[ASNN_CLASSES];
     {
@@ -867,7 +880,13 @@ __global__ __launch_bounds__(kMixedBlock) void workgroup_kernel(
                 for (int j = 0; j < VEC; ++j) part[wave][lane * VEC + j] = acc[j];
             }
             __syncthreads();
-            if (wave == 0 && lane < LPG) {
+            if constexpr (kSpread) {
+                if (wave == 0 && gsel < VEC) {            // lane group j adds up and finishes column j
+                    ACC s = ACC(0);
+                    for (int k = 0; k < kMixedWaves; ++k) s += part[k][(lane % LPG) * VEC + gsel];
+                    put_column(row, s);
+                }
+            } else if (wave == 0 && lane < LPG) {
                 float out[VEC];
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) {
@@ -883,7 +902,12 @@ __global__ __launch_bounds__(kMixedBlock) void workgroup_kernel(
         for (int row = mb + wave; row < lb; row += kMixedWaves) {
             ACC acc[VEC];
             row_sum<VEC, LPG, ACC, U>(cl, wt, Vr, ld, rp[row], rp[row + 1], cr, acc);
-            if (lane < LPG) {
+            if constexpr (kSpread) {
+                ACC mine = acc[0];
+#pragma unroll
+                for (int j = 1; j < VEC; ++j) mine = (gsel == j) ? acc[j] : mine;
+                if (gsel < VEC) put_column(row, mine);
+            } else if (lane < LPG) {
                 float out[VEC];
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) out[j] = squash(acc[j]);
