@@ -376,6 +376,35 @@ def test_saturation_gives_exact_zero_and_one(amd):
         assert (y[:3] == 0.0).all() and y[3] == 1.0
 
 
+def test_sigmoid_over_a_dense_range_of_sums(amd):
+    """One connection of weight 1 from a raw sensor into a node, for 200 000 sensor values across the
+    range where the sigmoid moves and out into both tails: the default mode must give the fp64
+    sigmoid rounded to fp32 (the last bit may differ where the fp64 value sits on a rounding
+    boundary: at most one float ulp, and rarely), NaN stays NaN, the far tails are exactly 0 and 1."""
+    from workloads import Workload
+    n = 2000
+    B = 100
+    rng = np.random.default_rng(5)
+    x = np.concatenate([np.linspace(-9.0, 9.0, n * B - 4000), rng.uniform(-200.0, 200.0, 3990),
+                        [np.nan, np.inf, -np.inf, 0.0, -0.0, 1e-30, -1e-30, 88.0, -88.0, 150.0]]).astype(np.float32)
+    x = x.reshape(n, B)
+    src = np.arange(n, dtype=np.int32)
+    dst = np.arange(n, 2 * n, dtype=np.int32)
+    wl = Workload("sigmoid", 2 * n, src, dst, np.ones(n, np.float32), src.copy(), dst.copy(), x)
+    with np.errstate(over="ignore"):
+        want = (1.0 / (1.0 + np.exp(-4.97 * x.astype(np.float64)))).astype(np.float32)
+    for flags in (LEVELS | 1, DATAFLOW | 1, WORKGROUP | 1):
+        _, V, Y = run_gpu(amd, wl, flags=flags)
+        got = Y.cpu().numpy()
+        nan = np.isnan(want)
+        assert (np.isnan(got) == nan).all()
+        diff = np.abs(got[~nan].astype(np.float64) - want[~nan])
+        ulp = np.spacing(want[~nan]).astype(np.float64)
+        assert (diff <= ulp).all(), float(diff.max())
+        assert (diff > 0).mean() < 1e-4, float((diff > 0).mean())
+        assert (got[x > 20] == 1.0).all() and (got[x < -40] == 0.0).all()
+
+
 def test_degenerate_networks(amd):
     from workloads import Workload
     # no connections at all: sensors squash, the other node gives 0.5
