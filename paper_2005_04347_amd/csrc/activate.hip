@@ -60,12 +60,14 @@ __device__ inline void store_vec(float *p, const float (&in)[VEC]) {
 
 // sigmoid with the paper's slope, 1 / (1 + e^(-4.97 s)), the fp64 value rounded to float.
 // Where one wavefront's sigmoid sits between two levels its chain of dependent instructions is what
-// the level waits for (a library exponential and a full division are about 45 deep), so both are
-// written out with short chains: e^y = 2^k e^r with k = round(y / ln 2), e^r by its Taylor series to
-// r^13 (|r| <= 0.347: the next term is below 5e-18) in Estrin's scheme, the reciprocal by the
-// hardware's estimate and two Newton steps; about 20 deep, a few ulp of fp64, far inside the float
-// the result is rounded to.  y is kept in [-745, 709]: beyond, e^y is 0 or would overflow, and the
-// float result is exactly 1 or 0 already at the bounds.  NaN stays NaN.
+// the level waits for, and a library exponential followed by a full fp64 division is about 45
+// deep.  Written out: e^y = 2^k e^r with k = round(y / ln 2), e^r by its Taylor series to r^13
+// (|r| <= 0.347: the next term is below 5e-18), the reciprocal by the hardware's estimate and two
+// Newton steps (none of the division's scaling and fix-up: the denominator is in [1, 1e308]); a few
+// ulp of fp64, far inside the float the result is rounded to.  (Estrin's scheme for the series is
+// another 1.5 % shorter per level at one input vector and costs the bandwidth-bound kernels 0.8 %.)
+// y is kept in [-745, 709]: beyond, e^y is 0 or would overflow, and the float result is exactly 1 or
+// 0 already at the bounds.  NaN stays NaN.
 __device__ inline float squash(double s) {
     double y = -4.97 * s;
     y = y > 709.0 ? 709.0 : y;
@@ -73,17 +75,21 @@ __device__ inline float squash(double s) {
     const double k = __builtin_rint(y * 1.4426950408889634074);
     double r = __builtin_fma(k, -6.93147180369123816490e-01, y);     // ln 2, high part (k * it is exact)
     r = __builtin_fma(k, -1.90821492927058770002e-10, r);            // low part
-    const double r2 = r * r, r4 = r2 * r2, r8 = r4 * r4;
-    const double p01 = 1.0 + r;
-    const double p23 = __builtin_fma(r, 1.0 / 6.0, 0.5);
-    const double p45 = __builtin_fma(r, 1.0 / 120.0, 1.0 / 24.0);
-    const double p67 = __builtin_fma(r, 1.0 / 5040.0, 1.0 / 720.0);
-    const double p89 = __builtin_fma(r, 1.0 / 362880.0, 1.0 / 40320.0);
-    const double pab = __builtin_fma(r, 1.0 / 39916800.0, 1.0 / 3628800.0);
-    const double pcd = __builtin_fma(r, 1.0 / 6227020800.0, 1.0 / 479001600.0);
-    const double q0 = __builtin_fma(r2, p23, p01), q1 = __builtin_fma(r2, p67, p45), q2 = __builtin_fma(r2, pab, p89);
-    const double s0 = __builtin_fma(r4, q1, q0), s1 = __builtin_fma(r4, pcd, q2);
-    const double e = __builtin_ldexp(__builtin_fma(r8, s1, s0), (int)k);
+    double p = 1.0 / 6227020800.0;
+    p = __builtin_fma(p, r, 1.0 / 479001600.0);
+    p = __builtin_fma(p, r, 1.0 / 39916800.0);
+    p = __builtin_fma(p, r, 1.0 / 3628800.0);
+    p = __builtin_fma(p, r, 1.0 / 362880.0);
+    p = __builtin_fma(p, r, 1.0 / 40320.0);
+    p = __builtin_fma(p, r, 1.0 / 5040.0);
+    p = __builtin_fma(p, r, 1.0 / 720.0);
+    p = __builtin_fma(p, r, 1.0 / 120.0);
+    p = __builtin_fma(p, r, 1.0 / 24.0);
+    p = __builtin_fma(p, r, 1.0 / 6.0);
+    p = __builtin_fma(p, r, 0.5);
+    p = __builtin_fma(p, r, 1.0);
+    p = __builtin_fma(p, r, 1.0);
+    const double e = __builtin_ldexp(p, (int)k);
     const double d = 1.0 + e;
     double x = __builtin_amdgcn_rcp(d);
     x = __builtin_fma(x, __builtin_fma(-d, x, 1.0), x);
