@@ -96,7 +96,8 @@ __device__ inline float squash(double s) {
     x = __builtin_fma(x, __builtin_fma(-d, x, 1.0), x);
     return (float)x;
 }
-__device__ inline float squash(float s) { return 1.0f / (1.0f + __expf(-4.97f * s)); }
+// (fast mode: hardware exponential and reciprocal, about an ulp each; e^(+big) = inf gives 0, never NaN)
+__device__ inline float squash(float s) { return __builtin_amdgcn_rcpf(1.0f + __expf(-4.97f * s)); }
 
 // ---- sums across the lane groups of a wavefront ---------------------------
 // Value of the lane SHIFT places further on in the same row of 16 lanes, wrapping round: one DPP
