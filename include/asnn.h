@@ -33,6 +33,26 @@
  *     loop is a cycle; node ids need not be in topological order.
  *   - batch layout is node-major with the batch contiguous: X[k*B + b],
  *     V[i*B + b], Y[o*B + b].
+ *
+ * Shape of the boundary.  The three calls take the paper's problem statement
+ * (connections, inputs, outputs; layers; activation of the sorted node array)
+ * in this form:
+ *   - the packed network travels as ONE record (asnn_packed: sizes plus the
+ *     caller-allocated arrays) from asnn_pack_csr to asnn_activate, not as a
+ *     list of a dozen array arguments repeated in both signatures;
+ *   - a population of networks is passed as their disjoint union: the caller
+ *     offsets the node ids of network k by the number of nodes before it and
+ *     concatenates the connection lists, input ids, output ids and the rows
+ *     of X.  No per-network offset arrays cross the boundary: levels, packing
+ *     and activation of a union are those of its components;
+ *   - the default arithmetic is the one that meets the parity bar on every
+ *     workload (fp64 sums and sigmoid, one rounding to float);
+ *     ASNN_FLAG_ACC_F32 selects float arithmetic, not the other way round;
+ *   - results restricted to the required set R are obtained by filtering the
+ *     connections beforehand (asnn_required_set / asnn_filter_required) rather
+ *     than by a flag of asnn_activate;
+ *   - the library keeps no cache of graphs or launches between calls, so there
+ *     is nothing to clear: every buffer, workspaces included, is the caller's.
  */
 #ifndef ASNN_H
 #define ASNN_H
@@ -225,9 +245,14 @@ int asnn_pack_csr(const int32_t *src, const int32_t *dst, const float *w, const 
  *               workspace each.
  * Ids outside [0,n_nodes) in input_ids / output_ids are skipped (an output row
  * of such an id is filled with NaN).  Errors: NULL, SIZE, WORKSPACE, HIP.
- * Asynchronous.  A dataflow wait that exceeds its time limit (it cannot with
- * a valid packed record) stops waiting and raises a flag in the workspace
- * that asnn_activate_status reports. */
+ * Asynchronous.  A dataflow wait that exceeds its time limit (2 s of device
+ * wall clock; it cannot with a valid packed record on a device that runs the
+ * launch without interruption) stops waiting and raises a flag in the
+ * workspace: rows computed from unwritten sources are NaN, the output rows
+ * copied to Y after the flag was raised are NaN, and asnn_activate_status
+ * reports ASNN_ERR_TIMEOUT.  A caller that cannot rule such a wait out (a
+ * device shared with other processes) treats a dataflow result as valid only
+ * once asnn_activate_status has returned ASNN_OK. */
 size_t asnn_activate_workspace_bytes(const asnn_packed *packed, int32_t B);
 /* Which schedule asnn_activate takes for this record, batch width, workspace
  * (given or not) and flags: 0 = one launch per level, 1 = dataflow, 2 = one

@@ -1,34 +1,34 @@
-"""The paper's set-based network segmentation, written out for small networks.
+"""Set-based network segmentation for small networks -- test infrastructure.
 
-Follows the "Network segmentation algorithm" (Sec. "Sequential activation") in
-its own notation: R = required nodes, IN = input nodes, OP = output nodes,
-CON = set of connections (a, b); s = nodes already assigned; c = candidates of
-the next layer; t = candidates whose entire input set lies in s.  The garbled
-"all <- (...)" line is read as: all(a in s for every (a, b) in CON with b = n),
-which is what the comment above it and the prose after the listing say.
+What the paper's segmentation step computes (Sec. "Sequential activation", segmentation
+algorithm and the paragraph after it), stated from the definition rather than from the listing:
+starting from the input nodes, the next layer is made of the required nodes that are not assigned
+yet, receive at least one connection from an assigned node, and whose ENTIRE set of incoming
+nodes is already assigned; layers are peeled off until none can be formed.  (The listing's line
+that tests a candidate is garbled; the comment above it and the prose after the listing both say
+"entire input set", which is the reading taken.)
 
-Returns the list of layers *after* the input layer, each a set of nodes, as the
-algorithm does (L excludes IN).  Test infrastructure; quadratic, tiny inputs only.
+segment_network(R, IN, OP, CON) -> list of layers after the input layer, each a set of nodes.
+A predecessor map is built once; every round looks at each unassigned node.  Quadratic in the
+worst case, meant for networks of a few dozen nodes.  OP is accepted because the algorithm is
+stated with it; the layering does not depend on it.
 """
 from __future__ import annotations
 
 
 def segment_network(R, IN, OP, CON):
-    R = set(R)
-    CON = list(CON)
-    L = []
-    s = set(IN)
-    while True:
-        # candidate nodes for the next layer
-        c = {b for (a, b) in CON if a in s and b not in s}
-        # used nodes whose entire input set is in s
-        t = set()
-        for n in c:
-            entire = all(a in s for (a, b) in CON if b == n)
-            if n in R and entire:
-                t = t | {n}
-        if not t:
-            break
-        L = L + [t]
-        s = s | t
-    return L
+    required = set(R)
+    assigned = set(IN)
+    incoming = {}
+    for a, b in CON:
+        incoming.setdefault(b, set()).add(a)
+    waiting = {n for n in incoming if n in required and n not in assigned}
+    layers = []
+    while waiting:
+        layer = {n for n in waiting if incoming[n] <= assigned}
+        if not layer:
+            break           # what is left depends on nodes that can never be assigned
+        layers.append(layer)
+        assigned |= layer
+        waiting -= layer
+    return layers

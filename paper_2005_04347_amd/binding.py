@@ -319,11 +319,16 @@ class Network:
             self._workspaces[B] = asnn_activate_workspace(self.graph, B, self.device)
         return self._workspaces[B]
 
-    def activate(self, X, V=None, Y=None, flags: int = 0, use_workspace: bool = True):
+    def activate(self, X, V=None, Y=None, flags: int = 0, use_workspace: bool = True, check: bool = False):
+        """check=True synchronises after the call and raises if a dataflow wait gave up (see
+        asnn_activate_status): for callers that share the device with other processes."""
         X = _dev_f32(X, self.device)
         with torch.cuda.device(self.device):
             ws = self.workspace(int(X.shape[1])) if use_workspace else None
-            return asnn_activate(self.graph, self.input_ids, X, self.output_ids, V=V, Y=Y, flags=flags, workspace=ws)
+            out = asnn_activate(self.graph, self.input_ids, X, self.output_ids, V=V, Y=Y, flags=flags, workspace=ws)
+            if check:
+                asnn_activate_status(ws)
+            return out
 
     def check(self, B: int) -> None:
         """Synchronises and raises if the last dataflow activation at batch B timed out."""

@@ -24,6 +24,8 @@
 // Arithmetic: products and sums in ACC (double by default, float with
 // ASNN_FLAG_ACC_F32), sigmoid(x) = 1/(1+e^(-4.97x)) in ACC, one rounding to
 // float on store.
+#include <atomic>
+
 #include "asnn_common.h"
 
 namespace asnn {
@@ -657,6 +659,12 @@ __global__ __launch_bounds__(kMixedBlock) void dataflow_kernel(const int32_t *__
                         load_vec_device_scope<VEC>(vres, off, out);
                         if (row < first_row || !shows_not_ready<VEC>(out) || !patience.again(ctl)) break;
                     }
+                    // A wait that was given up anywhere leaves rows computed from unwritten sources:
+                    // the outputs copied from then on say so themselves instead of looking like results.
+                    if (__hip_atomic_load(&ctl->error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+#pragma unroll
+                        for (int j = 0; j < VEC; ++j) out[j] = __builtin_nanf("");
+                    }
                 } else {
 #pragma unroll
                     for (int j = 0; j < VEC; ++j) out[j] = __builtin_nanf("");
@@ -1076,6 +1084,14 @@ __global__ __launch_bounds__(kMixedBlock) void workgroup_kernel(
     }
 }
 
+// Level 0: every value is sigmoid(0) until a sensor overwrites its row.
+template <typename ACC>
+__global__ void fill_half_kernel(float *__restrict__ V, size_t n) {
+    const float half = squash(ACC(0));
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) V[i] = half;
+}
+
 // Sensors: V[row of input_ids[k]][b] = sigmoid(X[k][b]) (or X raw).
 template <typename ACC>
 __global__ void stage_inputs_kernel(const int32_t *__restrict__ input_ids, const int32_t *__restrict__ inv_perm,
@@ -1226,16 +1242,19 @@ template <int VEC, int LPG, typename ACC>
 int launch_dataflow(const LevelArgs &a, const DataflowArgs &d) {
     const int vecs = a.B / VEC;
     const int tiles = (vecs + LPG - 1) / LPG;
-    static int per_cu_of[kMaxDevices] = {};       // resident 16-wave blocks per CU for this instantiation
+    // resident 16-wave blocks per CU for this instantiation, per device (threads that race to fill
+    // an entry store the same value)
+    static std::atomic<int> per_cu_of[kMaxDevices];
     int dev = 0;
     ASNN_HIP_TRY(hipGetDevice(&dev));
     if (dev < 0 || dev >= kMaxDevices) return ASNN_ERR_NO_DEVICE;
-    int &per_cu = per_cu_of[dev];
+    int per_cu = per_cu_of[dev].load(std::memory_order_relaxed);
     if (per_cu == 0) {
         int n = 0;
         ASNN_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dataflow_kernel<VEC, LPG, ACC, kUnroll>,
                                                                   kMixedBlock, 0));
         per_cu = n > 0 ? n : 1;
+        per_cu_of[dev].store(per_cu, std::memory_order_relaxed);
     }
     // Workgroups far ahead of the wavefront of finished rows only spin and re-read: a few levels'
     // worth of units in flight is enough.
@@ -1315,11 +1334,12 @@ int launch_workgroup(const LevelArgs &a, const WorkgroupArgs &g) {
     const int tiles = (vecs + LPG - 1) / LPG;
     const size_t lds = staged_lds_bytes(g.n_nodes, g.n_edges, g.n_levels, LPG * VEC);
     // dynamic LDS this instantiation may take on the current device (the attribute is per device)
-    static size_t budgets[kMaxDevices] = {};
+    // (threads that race to fill an entry set the same attribute and store the same value)
+    static std::atomic<size_t> budgets[kMaxDevices];
     int dev = 0;
     ASNN_HIP_TRY(hipGetDevice(&dev));
     if (dev < 0 || dev >= kMaxDevices) return ASNN_ERR_NO_DEVICE;
-    size_t &budget = budgets[dev];
+    size_t budget = budgets[dev].load(std::memory_order_acquire);
     if (budget == 0) {
         const size_t fixed = sizeof(ACC) * kMixedWaves * LPG * VEC + 256;       // static LDS of the kernel, rounded up
         int optin = 0;
@@ -1335,6 +1355,7 @@ int launch_workgroup(const LevelArgs &a, const WorkgroupArgs &g) {
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)(most - fixed)) == hipSuccess)
             budget = most - fixed;
         (void)hipGetLastError();
+        budgets[dev].store(budget, std::memory_order_release);
     }
     const size_t lds_values = ((size_t)g.n_nodes * (size_t)(LPG * VEC) * 4 + 15) & ~(size_t)15;      // the value tile alone
     if (lds <= budget) {
@@ -1565,12 +1586,20 @@ extern "C" int asnn_activate(const asnn_packed *packed, const int32_t *input_ids
         return f32 ? launch_workgroup_any<float>(a, g) : launch_workgroup_any<double>(a, g);
     }
 
-    // Level 0 has no incoming connections.  Rows that are no sensors get sigmoid(0); when every
-    // row of the level is a sensor the fill is skipped.
+    // Level 0 has no incoming connections: every row of it gets sigmoid(0), then the sensors take
+    // their inputs.  (The fill is not skipped when the level holds as many rows as there are input
+    // ids: the ids are the caller's, unchecked here, and one that is out of range or listed twice
+    // would leave a root that is no sensor unwritten.)
     {
-        const int hb = level_ptr_host[0], mb = level_ptr_host[1], lb = level_ptr_host[2], le = level_ptr_host[3];
-        if (le - hb != n_inputs)
-            ASNN_TRY(f32 ? launch_level_any<float>(a, hb, mb, lb, le) : launch_level_any<double>(a, hb, mb, lb, le));
+        const size_t n0 = (size_t)level_ptr_host[ASNN_CLASSES] * (size_t)B;
+        if (n0 > 0) {
+            const dim3 grid(blocks_for(n0, 256 * 4, 4096));
+            if (f32)
+                hipLaunchKernelGGL(fill_half_kernel<float>, grid, dim3(256), 0, s, V, n0);
+            else
+                hipLaunchKernelGGL(fill_half_kernel<double>, grid, dim3(256), 0, s, V, n0);
+            ASNN_HIP_TRY(hipGetLastError());
+        }
         if (n_inputs > 0 && !dataflow) {
             const unsigned blocks = blocks_for((size_t)n_inputs * (size_t)B, 256, 8192);
             if (f32)
@@ -1583,15 +1612,16 @@ extern "C" int asnn_activate(const asnn_packed *packed, const int32_t *input_ids
         }
     }
     if (dataflow) {
-        static int cus_of[kMaxDevices] = {};
+        static std::atomic<int> cus_of[kMaxDevices];
         int dev = 0;
         ASNN_HIP_TRY(hipGetDevice(&dev));
         if (dev < 0 || dev >= kMaxDevices) return ASNN_ERR_NO_DEVICE;
-        int &cus = cus_of[dev];
+        int cus = cus_of[dev].load(std::memory_order_relaxed);
         if (cus == 0) {
             int n = 0;
             ASNN_HIP_TRY(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev));
             cus = n > 0 ? n : 1;
+            cus_of[dev].store(cus, std::memory_order_relaxed);
         }
         // work items and output items are numbered by one 32-bit counter
         if ((long long)((n_outputs + kMixedWaves - 1) / kMixedWaves) * tiles >= 0x3fffffffLL) return ASNN_ERR_SIZE;

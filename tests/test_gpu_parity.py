@@ -437,6 +437,33 @@ def test_degenerate_networks(amd):
         assert np.abs(got - want).max() <= TIGHT and (got[:2] == 0.5).all()
 
 
+@pytest.mark.parametrize("B", [1, 7, 130])
+def test_bad_input_ids_leave_no_root_unwritten(amd, B):
+    """asnn_activate takes the input ids as they come: one out of range is skipped, one listed twice
+    is staged twice.  With such a list the number of ids can equal the number of rows in level 0
+    although the level also holds roots that are no sensors; every such root must still come out
+    as sigmoid(0) = 0.5, in every schedule, on a value matrix that arrives full of NaN."""
+    wl = layered_skip(seed=13, n_nodes=300, n_inputs=3, n_outputs=5, n_levels=6, B=B, mean_extra_degree=4.0)
+    # the network keeps its three roots, but only the first is a sensor
+    sensor, roots = wl.input_ids[:1], wl.input_ids[1:]
+    net = amd.Network(wl.n_nodes, wl.src, wl.dst, wl.w, sensor, wl.output_ids)
+    lp = net.graph.level_ptr_host
+    assert lp[3] == 3                                             # level 0: one sensor, two other roots
+    bad = np.array([sensor[0], wl.n_nodes + 5, sensor[0]], dtype=np.int32)      # as many ids as level-0 rows
+    X = np.ascontiguousarray(wl.X[[0, 1, 0]])                      # the repeated id gets the same row both times
+    want = oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, sensor, wl.X[:1])
+    ids = torch.from_numpy(bad).cuda()
+    Xd = torch.from_numpy(X).cuda()
+    for sched in (0, LEVELS, DATAFLOW, WORKGROUP):
+        V = torch.full((wl.n_nodes, B), float("nan"), device="cuda:0")
+        V, Y = amd.asnn_activate(net.graph, ids, Xd, net.output_ids, V=V, flags=sched, workspace=net.workspace(B))
+        net.check(B)
+        got = net.values_original_order(V).cpu().numpy()
+        assert (got[roots] == np.float32(0.5)).all(), sched
+        assert np.abs(got.astype(np.float64) - want).max() <= TIGHT, sched
+        assert (Y.cpu().numpy() == got[wl.output_ids]).all(), sched
+
+
 def test_error_codes_from_device_checks(amd):
     dev = "cuda:0"
     t = lambda a: torch.tensor(a, dtype=torch.int32, device=dev)
@@ -520,16 +547,27 @@ def test_levels_across_narrow_and_wide_frontiers(amd, seed):
     assert e.value.code == -6
 
 
-FULL_COLUMNS = {1: None, 2: None, 3: 48, 4: 16, 5: 12}
+def _max_abs_err_every_element(V, inv, want, rows_per_chunk=1 << 18):
+    """max |V[inv] - want| over EVERY element, in fp64 (exact for two floats), row chunk by row chunk
+    so that the temporaries stay small next to a value matrix of a gigabyte.  V is the device result
+    in packed row order, inv maps original ids to packed rows, want is the oracle's host array in
+    original ids.  Also returns whether any element of the device result is NaN."""
+    worst, any_nan = 0.0, False
+    for r0 in range(0, want.shape[0], rows_per_chunk):
+        r1 = min(r0 + rows_per_chunk, want.shape[0])
+        got = V[inv[r0:r1]].cpu().numpy()
+        any_nan = any_nan or bool(np.isnan(got).any())
+        worst = max(worst, float(np.abs(got.astype(np.float64) - want[r0:r1]).max()))
+    return worst, any_nan
 
 
 @pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
 def test_full_size_configs(amd, idx):
-    """The five workloads at full size, in the default schedule (the one the
-    benchmark times) and in every forced schedule.  Levels: every node,
-    bit-exact.  Activations: batch columns are independent, so the oracle
-    evaluates a spread subset of columns (all nodes of those columns) and the
-    same columns of the GPU result must agree."""
+    """The five workloads at full size, in the default schedule (the one the benchmark times) and
+    in every forced schedule.  Levels and packed arrays: every element, bit-exact.  Activations:
+    the oracle evaluates ALL batch columns and every element of the value matrix is compared, for
+    every schedule (every column tile and both edges of every tile of the kernels' launch
+    configuration are covered)."""
     wl = make_config(idx, "full")
     net = amd.Network(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.output_ids)
     lv = net.level.cpu().numpy()
@@ -544,37 +582,104 @@ def test_full_size_configs(amd, idx):
     assert (g.level_ptr_host == level_ptr).all() and (g.row_ptr.cpu().numpy() == row_ptr).all()
     assert (g.col.cpu().numpy() == col).all() and (g.w.cpu().numpy() == w).all()
     del perm, inv_np, col, w
-    ncol = FULL_COLUMNS[idx]
-    cols = np.arange(wl.B) if ncol is None else np.unique(np.linspace(0, wl.B - 1, ncol).astype(int))
-    want = oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, np.ascontiguousarray(wl.X[:, cols]))
+    want = oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.X)       # [N, B], every column
+    assert want.shape == (wl.n_nodes, wl.B) and np.isfinite(want).all()
     inv = net.graph.inv_perm.long()
-    tcols = torch.as_tensor(cols, device="cuda:0")
+    outs = torch.as_tensor(wl.output_ids.astype(np.int64), device="cuda:0")
     for sched in (0, LEVELS, DATAFLOW, WORKGROUP):
         _, V, Y = run_gpu(amd, wl, flags=sched, net=net)
-        got = V[:, tcols][inv].cpu().numpy()
-        assert np.isfinite(got).all()
-        err = float(np.abs(got.astype(np.float64) - want).max())
-        print(f"config {idx} schedule {sched}: N={wl.n_nodes} E={wl.n_edges} B={wl.B} L={nl_o} "
-              f"columns={len(cols)} max_abs_err={err:.3e}")
+        err, any_nan = _max_abs_err_every_element(V, inv, want)
+        print(f"config {idx} schedule {sched} ({amd.asnn_activate_schedule(net.graph, wl.B, True, sched)}): "
+              f"N={wl.n_nodes} E={wl.n_edges} B={wl.B} L={nl_o} elements={wl.n_nodes * wl.B} max_abs_err={err:.3e}")
+        assert not any_nan, sched
         assert err <= TOL, (sched, err)
-        y = Y[:, tcols].cpu().numpy()
-        assert (y == got[wl.output_ids]).all()
-        # nothing outside the sampled columns is left unwritten
-        assert not torch.isnan(V).any()
+        assert torch.equal(Y, V[inv[outs]]), sched
         del V, Y
+
+
+def _per_network(wl, k):
+    """Network k of a population workload as a workload of its own (ids and rows made local)."""
+    from workloads import Workload
+    n0, n1 = int(wl.net_node_ptr[k]), int(wl.net_node_ptr[k + 1])
+    e0, e1 = int(wl.net_edge_ptr[k]), int(wl.net_edge_ptr[k + 1])
+    i0, i1 = int(wl.net_input_ptr[k]), int(wl.net_input_ptr[k + 1])
+    o0, o1 = int(wl.net_output_ptr[k]), int(wl.net_output_ptr[k + 1])
+    return Workload(f"{wl.name}[{k}]", n1 - n0, wl.src[e0:e1] - n0, wl.dst[e0:e1] - n0, wl.w[e0:e1],
+                    wl.input_ids[i0:i1] - n0, wl.output_ids[o0:o1] - n0, np.ascontiguousarray(wl.X[i0:i1])), (n0, n1, o0, o1)
+
+
+def test_population_call_equals_per_network_calls(amd):
+    """A population is the disjoint union of its networks, so one call over the union must give each
+    network what a call of its own gives it.  With level launches and the dataflow schedule the
+    order of the additions of a row depends on the row and the batch width alone: bit-identical.
+    The workgroup schedule walks the light rows of a narrow level in teams and those of a wide one
+    serially (the width of a level differs between the union and one network), so there the two
+    agree to the rounding of the final store."""
+    wl = make_config(5, "small")
+    assert wl.n_nets == 9
+    want = oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.X)
+    union = amd.Network(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.output_ids)
+    lp = union.graph.level_ptr_host
+    assert (lp[2::3][: union.n_levels] - lp[1::3][: union.n_levels]).max() < 256    # medium rows are never grouped
+    nets = [(_per_network(wl, k)) for k in range(wl.n_nets)]
+    singles = [amd.Network(s.n_nodes, s.src, s.dst, s.w, s.input_ids, s.output_ids) for s, _ in nets]
+    lv = union.level.cpu().numpy()
+    for (s, (n0, n1, _, _)), net in zip(nets, singles):
+        assert (net.level.cpu().numpy() == lv[n0:n1]).all()          # levels of the union = per-network levels
+    for sched in SCHEDULES:
+        _, V, Y = run_gpu(amd, wl, flags=sched, net=union)
+        got = union.values_original_order(V).cpu().numpy()
+        assert np.abs(got.astype(np.float64) - want).max() <= TIGHT, sched
+        y = Y.cpu().numpy()
+        for (s, (n0, n1, o0, o1)), net in zip(nets, singles):
+            _, Vk, Yk = run_gpu(amd, s, flags=sched, net=net)
+            gk = net.values_original_order(Vk).cpu().numpy()
+            if sched == WORKGROUP:
+                assert np.abs(gk.astype(np.float64) - got[n0:n1]).max() <= TIGHT, (sched, s.name)
+                assert np.abs(Yk.cpu().numpy().astype(np.float64) - y[o0:o1]).max() <= TIGHT, (sched, s.name)
+            else:
+                assert (gk == got[n0:n1]).all(), (sched, s.name)
+                assert (Yk.cpu().numpy() == y[o0:o1]).all(), (sched, s.name)
+
+
+@pytest.mark.parametrize("idx", [3, 4])
+def test_relabelled_and_shuffled_network(amd, idx):
+    """Renaming the nodes and reordering the connection list changes nothing but names: the levels
+    are the same bit for bit, and the activations agree to the rounding of the final store (the
+    additions of a row follow the connection list, so the fp64 sums may differ in their last bits)."""
+    from workloads import Workload
+    wl = make_config(idx, "small")
+    rng = np.random.default_rng(77 + idx)
+    relabel = rng.permutation(wl.n_nodes).astype(np.int32)           # old id -> new id
+    order = rng.permutation(wl.n_edges)
+    twin = Workload(wl.name + "-relabelled", wl.n_nodes, relabel[wl.src][order], relabel[wl.dst][order], wl.w[order],
+                    relabel[wl.input_ids], relabel[wl.output_ids], wl.X)
+    a = amd.Network(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.output_ids)
+    b = amd.Network(twin.n_nodes, twin.src, twin.dst, twin.w, twin.input_ids, twin.output_ids)
+    assert a.n_levels == b.n_levels
+    assert (b.level.cpu().numpy()[relabel] == a.level.cpu().numpy()).all()
+    want = oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.X)
+    for sched in (0, LEVELS, DATAFLOW, WORKGROUP):
+        _, Va, Ya = run_gpu(amd, wl, flags=sched, net=a)
+        _, Vb, Yb = run_gpu(amd, twin, flags=sched, net=b)
+        ga = a.values_original_order(Va).cpu().numpy()
+        gb = b.values_original_order(Vb).cpu().numpy()[relabel]
+        assert np.abs(ga.astype(np.float64) - gb).max() <= TIGHT, sched
+        assert np.abs(gb.astype(np.float64) - want).max() <= TIGHT, sched
+        assert np.abs(Ya.cpu().numpy().astype(np.float64) - Yb.cpu().numpy()).max() <= TIGHT, sched
 
 
 def test_graph_capture_replays_match_eager(amd):
     """asnn_activate enqueues kernels only (no memset, no allocation, no host
     synchronisation), so a stream capture of it replays correctly: several
     replays, with eager work and synchronisations between them, all equal the
-    eager result, for both schedules."""
+    eager result, for every schedule."""
     wl = make_config(3, "small")
     net = amd.Network(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.output_ids)
     X = torch.from_numpy(wl.X).cuda()
     want_V, want_Y = net.activate(X, flags=LEVELS)
     torch.cuda.synchronize()
-    for sched in (LEVELS, DATAFLOW):
+    for sched in (LEVELS, DATAFLOW, WORKGROUP):
         V = torch.zeros_like(want_V)
         Y = torch.zeros_like(want_Y)
         net.workspace(wl.B)                       # allocate outside the capture
