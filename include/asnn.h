@@ -76,6 +76,7 @@ extern "C" {
 #define ASNN_ERR_LEVEL_ORDER (-9)        /* level[] is not increasing along a connection */
 #define ASNN_ERR_NO_DEVICE (-10)         /* no HIP device available */
 #define ASNN_ERR_TIMEOUT (-11)           /* a dataflow wait exceeded its time limit */
+#define ASNN_ERR_SCRATCH (-12)           /* asnn_activate_static: the network and batch need more scratch than it holds */
 
 /* asnn_activate flags */
 #define ASNN_FLAG_RAW_INPUTS 1u  /* store sensor inputs unsquashed (the paper squashes them) */
@@ -268,6 +269,36 @@ int asnn_activate(const asnn_packed *packed,
 /* Synchronises the stream and returns ASNN_OK, or ASNN_ERR_TIMEOUT if the last
  * dataflow activation that used this workspace gave up a wait.  NULL workspace: ASNN_OK. */
 int asnn_activate_status(const void *workspace, void *stream);
+
+/* ---- 3b. activate without any allocation ------------------------------------
+ * For callers that cannot allocate device memory or carry a workspace around:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  asnn_activate_static is asnn_activate (same arguments, same
+ * schedules, same kernels, same bits) with the workspace taken from a
+ * file-scope device array of ASNN_STATIC_SCRATCH_BYTES inside the library, one
+ * copy per device, which that device holds from the moment the library's code
+ * is loaded on it until the process ends.  The call itself allocates and frees
+ * nothing and calls no allocating routine; the caller still passes X, V and Y.
+ *   - A network and batch width whose asnn_activate_workspace_bytes() exceeds
+ *     ASNN_STATIC_SCRATCH_BYTES is refused with ASNN_ERR_SCRATCH, whatever
+ *     schedule would have been taken (only networks with rows of more than 512
+ *     connections need more than 512 bytes: n_edges*B/32 bytes, B rounded up
+ *     to whole tiles).  Nothing is launched then.
+ *   - Every call on a device shares that device's array, which still holds the
+ *     previous call's contents; the call resets what it uses.  Two calls that
+ *     may overlap in time on one device (different streams, different host
+ *     threads) race on it: such callers serialise them or use asnn_activate
+ *     with a workspace each.
+ *   - asnn_activate_status(ASNN_STATIC_SCRATCH, stream) reports an abandoned
+ *     dataflow wait of the last such call on the current device.
+ * Errors: those of asnn_activate, plus SCRATCH.  Asynchronous. */
+#define ASNN_STATIC_SCRATCH_BYTES (32u << 20)
+#define ASNN_STATIC_SCRATCH ((const void *)(uintptr_t)1)
+int asnn_activate_static(const asnn_packed *packed,
+                         const int32_t *input_ids, int32_t n_inputs,
+                         const int32_t *output_ids, int32_t n_outputs,
+                         const float *X, int32_t B, float *V, float *Y,
+                         uint32_t flags, void *stream);
 
 /* ---- yardstick -----------------------------------------------------------
  * Plain streaming device-to-device copy of `bytes` bytes (a multiple of 16,

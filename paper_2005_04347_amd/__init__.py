@@ -15,8 +15,11 @@ from .binding import (  # noqa: F401
     MEDIUM_INDEGREE,
     Network,
     PackedGraph,
+    STATIC_SCRATCH,
+    STATIC_SCRATCH_BYTES,
     asnn_activate,
     asnn_activate_schedule,
+    asnn_activate_static,
     asnn_activate_status,
     asnn_activate_workspace,
     asnn_build_levels,

@@ -29,15 +29,17 @@ CLASSES = 3
 ERR_NAMES = {
     -1: "ASNN_ERR_NULL", -2: "ASNN_ERR_SIZE", -3: "ASNN_ERR_INDEX", -4: "ASNN_ERR_INPUT_HAS_INEDGE",
     -5: "ASNN_ERR_DUP_INPUT", -6: "ASNN_ERR_CYCLE", -7: "ASNN_ERR_WORKSPACE", -8: "ASNN_ERR_HIP",
-    -9: "ASNN_ERR_LEVEL_ORDER", -10: "ASNN_ERR_NO_DEVICE", -11: "ASNN_ERR_TIMEOUT",
+    -9: "ASNN_ERR_LEVEL_ORDER", -10: "ASNN_ERR_NO_DEVICE", -11: "ASNN_ERR_TIMEOUT", -12: "ASNN_ERR_SCRATCH",
 }
+STATIC_SCRATCH_BYTES = 32 << 20
+STATIC_SCRATCH = 1          # ASNN_STATIC_SCRATCH: names the library's own scratch in asnn_activate_status
 
 EXPORTS = [
     "asnn_strerror", "asnn_last_hip_error", "asnn_version",
     "asnn_levels_workspace_bytes", "asnn_build_levels",
     "asnn_required_workspace_bytes", "asnn_required_set", "asnn_filter_workspace_bytes", "asnn_filter_required",
     "asnn_pack_workspace_bytes", "asnn_pack_csr", "asnn_activate_workspace_bytes", "asnn_activate",
-    "asnn_activate_status", "asnn_activate_schedule", "asnn_device_copy",
+    "asnn_activate_status", "asnn_activate_schedule", "asnn_activate_static", "asnn_device_copy",
 ]
 
 
@@ -89,6 +91,8 @@ def load() -> ctypes.CDLL:
     lib.asnn_activate_workspace_bytes.argtypes = [ctypes.POINTER(AsnnPacked), i32]
     lib.asnn_activate.restype = ctypes.c_int
     lib.asnn_activate.argtypes = [ctypes.POINTER(AsnnPacked), vp, i32, vp, i32, vp, i32, vp, vp, vp, sz, u32, vp]
+    lib.asnn_activate_static.restype = ctypes.c_int
+    lib.asnn_activate_static.argtypes = [ctypes.POINTER(AsnnPacked), vp, i32, vp, i32, vp, i32, vp, vp, u32, vp]
     lib.asnn_activate_schedule.restype = ctypes.c_int
     lib.asnn_activate_schedule.argtypes = [ctypes.POINTER(AsnnPacked), i32, ctypes.c_int, u32]
     lib.asnn_activate_status.restype = ctypes.c_int
@@ -265,6 +269,25 @@ def asnn_activate(g: PackedGraph, input_ids: torch.Tensor, X: torch.Tensor,
     return V, Y
 
 
+def asnn_activate_static(g: PackedGraph, input_ids: torch.Tensor, X: torch.Tensor, V: torch.Tensor,
+                         output_ids: Optional[torch.Tensor] = None, Y: Optional[torch.Tensor] = None, flags: int = 0):
+    """asnn_activate with the library's own scratch in the place of a workspace.  The binding allocates
+    nothing either: the caller brings V (and Y when output_ids is given).  Returns (V, Y)."""
+    lib = load()
+    assert X.dim() == 2 and X.dtype == torch.float32 and X.is_contiguous()
+    B = int(X.shape[1])
+    n_in = int(input_ids.numel())
+    assert X.shape[0] == n_in
+    assert V.shape == (g.n_nodes, B) and V.is_contiguous() and V.dtype == torch.float32
+    n_out = 0 if output_ids is None else int(output_ids.numel())
+    assert n_out == 0 or (Y is not None and Y.shape == (n_out, B) and Y.is_contiguous() and Y.dtype == torch.float32)
+    rc = lib.asnn_activate_static(ctypes.byref(g.record), _ptr(input_ids), n_in, _ptr(output_ids), n_out, _ptr(X), B,
+                                  ctypes.c_void_p(V.data_ptr()), _ptr(Y), flags, _stream())
+    if rc != 0:
+        raise AsnnError(rc, "asnn_activate_static")
+    return V, Y
+
+
 def asnn_activate_schedule(g: PackedGraph, B: int, has_workspace: bool = True, flags: int = 0) -> str:
     """'levels', 'dataflow' or 'workgroup': the schedule asnn_activate would take."""
     lib = load()
@@ -277,7 +300,11 @@ def asnn_activate_schedule(g: PackedGraph, B: int, has_workspace: bool = True, f
 def asnn_activate_status(workspace: Optional[torch.Tensor]) -> None:
     """Synchronises the current stream; raises if a dataflow wait of the last activation gave up."""
     lib = load()
-    rc = lib.asnn_activate_status(None if workspace is None else ctypes.c_void_p(workspace.data_ptr()), _stream())
+    if isinstance(workspace, int):       # STATIC_SCRATCH
+        ws = ctypes.c_void_p(workspace)
+    else:
+        ws = None if workspace is None else ctypes.c_void_p(workspace.data_ptr())
+    rc = lib.asnn_activate_status(ws, _stream())
     if rc != 0:
         raise AsnnError(rc, "asnn_activate_status")
 

@@ -1537,12 +1537,56 @@ extern "C" size_t asnn_activate_workspace_bytes(const asnn_packed *packed, int32
     return carve_activate(nullptr, packed, B).bytes;
 }
 
+// ---- scratch of the entry point that allocates nothing ---------------------
+// asnn_activate_static runs asnn_activate with this array in the place of the caller's workspace
+// (the control block of the dataflow schedule and the partial sums of split heavy rows).  The
+// array's name is only a host-side handle: its device address is looked up once per device, with
+// that device current, and from then on only that address is used (every device holds its own
+// copy of the array at its own address).
+static __device__ __align__(256) unsigned char scratch[ASNN_STATIC_SCRATCH_BYTES];
+
+namespace asnn {
+namespace {
+int static_scratch(void **out) {
+    static std::atomic<void *> address_of[kMaxDevices];
+    int dev = 0;
+    ASNN_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return ASNN_ERR_NO_DEVICE;
+    void *p = address_of[dev].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        ASNN_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (p == nullptr || ((uintptr_t)p & 255u) != 0) return ASNN_ERR_WORKSPACE;
+        address_of[dev].store(p, std::memory_order_release);      // (racing threads store the same address)
+    }
+    *out = p;
+    return ASNN_OK;
+}
+}  // namespace
+}  // namespace asnn
+
 extern "C" int asnn_activate_status(const void *workspace, void *stream) {
     ASNN_HIP_TRY(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
     if (!workspace) return ASNN_OK;
+    if (workspace == ASNN_STATIC_SCRATCH) {
+        void *p = nullptr;
+        ASNN_TRY(static_scratch(&p));
+        workspace = p;
+    }
     DataflowCtl host;
     ASNN_HIP_TRY(hipMemcpy(&host, workspace, sizeof(host), hipMemcpyDeviceToHost));
     return (host.magic == kCtlMagic && host.error) ? ASNN_ERR_TIMEOUT : ASNN_OK;
+}
+
+extern "C" int asnn_activate_static(const asnn_packed *packed, const int32_t *input_ids, int32_t n_inputs,
+                                    const int32_t *output_ids, int32_t n_outputs, const float *X, int32_t B,
+                                    float *V, float *Y, uint32_t flags, void *stream) {
+    if (!packed) return ASNN_ERR_NULL;
+    if (packed->n_nodes <= 0 || packed->n_edges < 0 || B <= 0) return ASNN_ERR_SIZE;
+    if (asnn_activate_workspace_bytes(packed, B) > (size_t)ASNN_STATIC_SCRATCH_BYTES) return ASNN_ERR_SCRATCH;
+    void *p = nullptr;
+    ASNN_TRY(static_scratch(&p));
+    return asnn_activate(packed, input_ids, n_inputs, output_ids, n_outputs, X, B, V, Y, p,
+                         (size_t)ASNN_STATIC_SCRATCH_BYTES, flags, stream);
 }
 
 extern "C" int asnn_activate(const asnn_packed *packed, const int32_t *input_ids, int32_t n_inputs,

@@ -24,6 +24,7 @@ extern "C" const char *asnn_strerror(int code) {
         case ASNN_ERR_LEVEL_ORDER: return "level[] does not increase along a connection";
         case ASNN_ERR_NO_DEVICE: return "no HIP device available";
         case ASNN_ERR_TIMEOUT: return "a dataflow wait exceeded its time limit";
+        case ASNN_ERR_SCRATCH: return "network and batch need more scratch than asnn_activate_static holds";
         default: return "unknown error";
     }
 }

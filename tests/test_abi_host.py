@@ -37,7 +37,7 @@ def test_every_declared_symbol_is_exported(lib):
 def test_error_strings(lib):
     assert lib.asnn_strerror(0) == b"ok"
     seen = set()
-    for code in range(-11, 0):
+    for code in range(-12, 0):
         s = lib.asnn_strerror(code)
         assert s and s != b"unknown error" and s not in seen
         seen.add(s)
@@ -183,3 +183,18 @@ def test_product_never_imports_the_oracle():
         if f.endswith((".py", ".c")):
             text = open(os.path.join(ROOT, "oracle", f)).read()
             assert "paper_2005_04347_amd" not in text and "libasnn.so" not in text, f
+
+
+def test_static_entry_point_refuses_on_the_host(lib):
+    """asnn_activate_static checks its arguments, and whether the network and batch fit the library's
+    scratch, before it touches a device."""
+    import paper_2005_04347_amd.binding as b
+    fake = ctypes.c_void_p(256)
+    assert lib.asnn_activate_static(None, fake, 1, fake, 1, fake, 4, fake, fake, 0, None) == -1
+    rec = b.AsnnPacked(n_nodes=1000, n_levels=3, n_edges=40_000_000, n_units=10, first_unit=1, max_heavy_indegree=4096)
+    assert lib.asnn_activate_workspace_bytes(ctypes.byref(rec), 64) > b.STATIC_SCRATCH_BYTES
+    assert lib.asnn_activate_static(ctypes.byref(rec), fake, 1, fake, 1, fake, 64, fake, fake, 0, None) == -12
+    rec.n_nodes = 0
+    assert lib.asnn_activate_static(ctypes.byref(rec), fake, 1, fake, 1, fake, 64, fake, fake, 0, None) == -2
+    text = open(os.path.join(ROOT, "include", "asnn.h")).read()
+    assert int(re.search(r"#define ASNN_STATIC_SCRATCH_BYTES \((\d+)u << 20\)", text).group(1)) << 20 == b.STATIC_SCRATCH_BYTES
