@@ -44,17 +44,34 @@ def cpu_model():
     return "unknown CPU"
 
 
+KERNEL_SOURCES = ("paper_2005_04347_amd/csrc/activate.hip", "paper_2005_04347_amd/csrc/asnn_common.h")
+
+
+def kernel_source_sha256():
+    """Fingerprint of the sources the activation kernels are built from (ties a counter summary to the code it measured)."""
+    import hashlib
+    h = hashlib.sha256()
+    for rel in KERNEL_SOURCES:
+        h.update(open(os.path.join(ROOT, rel), "rb").read())
+    return h.hexdigest()
+
+
 def measured_traffic(config, flags):
-    """HBM bytes per level launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary of this
-    workload (counter runs cannot be made from inside this process); None when no summary covers it."""
+    """L2<->fabric bytes per launch (reads + writes, Infinity-Cache hits included) from the committed
+    rocprofv3 FETCH_SIZE / WRITE_SIZE summary of this workload: counter runs cannot be made from inside this
+    process.  None when no summary covers the workload, or when the summary was taken from other kernel
+    sources than the ones in this tree (it names the fingerprint of the sources it measured)."""
     import glob
     paths = glob.glob(os.path.join(ROOT, "profiles", f"*_config{config}_hbm_traffic.md"))
     if flags != 0 or not paths:
         return None
+    traffic, sha = None, None
     for line in open(paths[0]):
         if line.startswith("traffic_bytes_per_launch:"):
-            return float(line.split(":")[1])
-    return None
+            traffic = float(line.split(":")[1])
+        if line.startswith("kernel_source_sha256:"):
+            sha = line.split(":")[1].strip()
+    return traffic if sha == kernel_source_sha256() else None
 
 
 def paper_regime(flags=0):
@@ -204,20 +221,41 @@ def main():
         torch.cuda.synchronize()
         step = graph.replay
 
-    # yardstick: what a plain streaming copy sustains on this device (read + write bytes)
+    # yardsticks: what a plain streaming copy (read + write bytes), a plain streaming read and a random
+    # row gather in the launch shape of this workload's levels sustain on this device
+    def timed(fn, reps):
+        for _ in range(2):
+            fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e-3 / reps
+
     n_copy = 256 * 1024 * 1024
     ca = torch.empty(n_copy, dtype=torch.float32, device=dev)
     cb = torch.empty(n_copy, dtype=torch.float32, device=dev)
-    for _ in range(2):
-        amd.asnn_device_copy(cb, ca)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(5):
-        amd.asnn_device_copy(cb, ca)
-    e1.record()
-    torch.cuda.synchronize()
-    copy_gbps = 5 * 2.0 * 4.0 * n_copy / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    sink = torch.zeros(64, dtype=torch.float32, device=dev)
+    copy_gbps = 2.0 * 4.0 * n_copy / timed(lambda: amd.asnn_device_copy(cb, ca), 5) / 1e9
+    read_gbps = 4.0 * n_copy / timed(lambda: amd.asnn_device_read(ca, sink), 5) / 1e9
     del ca, cb
+    gather_gbps = None
+    n_upper = wl.n_nodes - int(net.graph.level_ptr_host[3])          # rows above level 0
+    if B % 64 == 0 and net.n_levels > 1 and n_upper > 0:
+        # the value matrix itself is the buffer (its size and row length are the workload's); one launch per
+        # level with that level's number of rows, every row gathering the average in-degree from random rows
+        # BELOW its level (a level only reads lower levels, so early levels gather from a small, cached prefix)
+        lp = net.graph.level_ptr_host
+        gathers = max(1, round(wl.n_edges / n_upper))
+        shape = [(int(lp[3 * l]), int(lp[3 * l + 3] - lp[3 * l])) for l in range(1, net.n_levels)]
+        V.uniform_(0.0, 1.0)
+
+        def gather_step():
+            for lvl, (below, rows) in enumerate(shape):
+                amd.asnn_device_gather(V[:below], rows, gathers, lvl, sink)
+        gather_gbps = sum(rows for _, rows in shape) * gathers * B * 4.0 / timed(gather_step, 5) / 1e9
 
     for _ in range(args.warmup):
         step()
@@ -250,6 +288,8 @@ def main():
     # level launches: one gather launch per level above the input level; the other schedules: one launch
     launches = max(net.n_levels - 1, 1) if taken == "levels" else 1
     traffic = measured_traffic(args.config, args.flags) if args.schedule == "auto" and not args.graph else None
+    avg_launch_s = dev_ms_med * 1e-3 / launches
+    counter_gbps = None if traffic is None else traffic / avg_launch_s / 1e9
     out = {
         "metric": "G edge*samples/s for full ASNN activation",
         "value": round(value, 3),
@@ -270,6 +310,13 @@ def main():
                    "preprocess_M_connections_per_s": round(wl.n_edges / ((levels_ms + pack_ms) * 1e-3) / 1e6, 1)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "achieved_is": "algorithmic bytes of the gather model (4 B per connection and sample, whether or "
+                                    "not the line came from a cache) per second of device time",
+                     "traffic_is": "L2<->fabric bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE (Infinity-Cache "
+                                   "hits included, so an upper bound on HBM bytes); null when profiles/ holds no "
+                                   "summary taken from these kernel sources",
+                     "counter_GBps": None if counter_gbps is None else round(counter_gbps, 1),
+                     "counter_frac": None if counter_gbps is None else round(counter_gbps / HBM_PEAK_GBPS, 4),
                      "kernel": {"dataflow": "dataflow_kernel (one persistent launch)",
                                 "workgroup": "workgroup_kernel (one launch, one workgroup per batch tile)",
                                 "levels": "gather_light_kernel / gather_mixed_kernel (one launch per level)"}[taken],
@@ -278,10 +325,24 @@ def main():
                      "avg_launch_us": round(dev_ms_med * 1e3 / launches, 3),
                      "algorithmic_bytes_per_step": alg_bytes, "device_ms_per_step_median": round(dev_ms_med, 4),
                      "device_ms_per_step_min": round(dev_ms[0], 4),
-                     "device_copy_GBps": round(copy_gbps, 1), "frac_of_device_copy": round(achieved / copy_gbps, 4)},
+                     "device_copy_GBps": round(copy_gbps, 1), "device_read_GBps": round(read_gbps, 1),
+                     "device_gather_GBps": None if gather_gbps is None else round(gather_gbps, 1),
+                     "frac_of_device_read": round(achieved / read_gbps, 4),
+                     "frac_of_device_gather": None if gather_gbps is None else round(achieved / gather_gbps, 4),
+                     "yardsticks_are": "copy: 1 GiB read + 1 GiB written; read: 1 GiB streamed; gather: one launch per level in the "
+                                       "level launches' shape, every row loading the average in-degree of random rows "
+                                       "below its level from the value matrix, no arithmetic"},
     }
     if not args.no_cpu:
         import oracle
+        # the sequential baseline: one thread, pinned to the core it is running on
+        pinned_to = None
+        try:
+            allowed = sorted(os.sched_getaffinity(0))
+            pinned_to = allowed[len(allowed) // 2]
+            os.sched_setaffinity(0, {pinned_to})
+        except (AttributeError, OSError):
+            pass
         # calibrate on 8 columns, then time as many columns as fit in about 15 s (columns are independent)
         probe = np.ascontiguousarray(wl.X[:, :min(B, 8)])
         oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, probe[:, :1])     # warm-up / build
@@ -290,19 +351,24 @@ def main():
         per_col = (time.perf_counter() - t0) / probe.shape[1]
         cols = int(max(1, min(B, 15.0 / max(per_col, 1e-9))))
         Xs = np.ascontiguousarray(wl.X[:, :cols])
-        # whole passes over the sample until about 10 s of CPU work are on the clock
-        cpu_s, passes = 0.0, 0
+        # whole passes over the sample until about 10 s of CPU work are on the clock; the figure is the
+        # oracle's own clock around its node loop (activation only: the adjacency lists it builds first
+        # are its preprocessing, as the levels and the packing are the GPU path's)
+        cpu_s, loop_s, passes = 0.0, 0.0, 0
         while cpu_s < 10.0 and passes < 1000:
+            tm = {}
             t0 = time.perf_counter()
-            oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, Xs)
+            oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, Xs, timing=tm)
             cpu_s += time.perf_counter() - t0
+            loop_s += tm["activation_seconds"]
             passes += 1
         out["cpu_baseline"] = {
-            "value": round(float(wl.n_edges) * cols * passes / cpu_s / 1e9, 4), "unit": "G edge*samples/s", "cores": 1,
+            "value": round(float(wl.n_edges) * cols * passes / loop_s / 1e9, 4), "unit": "G edge*samples/s", "cores": 1,
             "kind": "oracle",
             "sample": f"the same network, first {cols} of {B} batch columns (columns are independent), "
-                      f"{passes} passes in {cpu_s:.2f} s single-threaded on {os.cpu_count()} visible host cores "
-                      f"({cpu_model()}); each pass includes building the oracle's adjacency lists",
+                      f"{passes} passes, {loop_s:.2f} s in the oracle's node loop ({cpu_s:.2f} s with its adjacency "
+                      f"build), single thread" + (f" pinned to core {pinned_to}" if pinned_to is not None else "") +
+                      f", {os.cpu_count()} visible host cores ({cpu_model()})",
         }
     print(json.dumps(out))
 

@@ -300,13 +300,31 @@ int asnn_activate_static(const asnn_packed *packed,
                          const float *X, int32_t B, float *V, float *Y,
                          uint32_t flags, void *stream);
 
-/* ---- yardstick -----------------------------------------------------------
- * Plain streaming device-to-device copy of `bytes` bytes (a multiple of 16,
- * both pointers 16-byte aligned, buffers must not overlap).  Not part of the
- * method: the benchmark uses it to measure the copy bandwidth of the device
- * and to calibrate hardware byte counters against a kernel of known traffic
- * (reads `bytes`, writes `bytes`).  Errors: NULL, SIZE, HIP.  Asynchronous. */
+/* ---- yardsticks ----------------------------------------------------------
+ * Not part of the method: kernels of known traffic without the method's
+ * arithmetic, which the benchmark times beside the activation.  All
+ * asynchronous; errors: NULL, SIZE, HIP.
+ *
+ * asnn_device_copy: plain streaming device-to-device copy of `bytes` bytes (a
+ * multiple of 16, both pointers 16-byte aligned, buffers must not overlap):
+ * reads `bytes`, writes `bytes`.  Also the kernel of known traffic against
+ * which hardware byte counters are calibrated.
+ *
+ * asnn_device_read: plain streaming read of `bytes` bytes (a multiple of 16,
+ * 16-byte aligned); sink is a device float the kernel may write (it does not,
+ * for ordinary data).
+ *
+ * asnn_device_gather: random row gather in the launch shape of one level of
+ * the activation over a matrix buf[n_rows][row_floats] (row_floats a multiple
+ * of 64): one single-wavefront workgroup per (row, tile of 128 columns -- 64
+ * when row_floats is no multiple of 128), rows_per_launch rows, each
+ * wavefront loading its tile of `gathers` pseudo-random rows of buf (seeded;
+ * all tiles of a row pick the same rows).  Reads
+ * rows_per_launch * gathers * row_floats * 4 bytes, writes nothing. */
 int asnn_device_copy(void *dst, const void *src, size_t bytes, void *stream);
+int asnn_device_read(const void *src, size_t bytes, float *sink, void *stream);
+int asnn_device_gather(const float *buf, int32_t n_rows, int32_t row_floats, int32_t rows_per_launch,
+                       int32_t gathers, uint32_t seed, float *sink, void *stream);
 
 #ifdef __cplusplus
 }

@@ -24,6 +24,8 @@ from .binding import (  # noqa: F401
     asnn_activate_workspace,
     asnn_build_levels,
     asnn_device_copy,
+    asnn_device_gather,
+    asnn_device_read,
     asnn_filter_required,
     asnn_required_set,
     asnn_pack_csr,

@@ -40,6 +40,7 @@ EXPORTS = [
     "asnn_required_workspace_bytes", "asnn_required_set", "asnn_filter_workspace_bytes", "asnn_filter_required",
     "asnn_pack_workspace_bytes", "asnn_pack_csr", "asnn_activate_workspace_bytes", "asnn_activate",
     "asnn_activate_status", "asnn_activate_schedule", "asnn_activate_static", "asnn_device_copy",
+    "asnn_device_read", "asnn_device_gather",
 ]
 
 
@@ -99,6 +100,10 @@ def load() -> ctypes.CDLL:
     lib.asnn_activate_status.argtypes = [vp, vp]
     lib.asnn_device_copy.restype = ctypes.c_int
     lib.asnn_device_copy.argtypes = [vp, vp, sz, vp]
+    lib.asnn_device_read.restype = ctypes.c_int
+    lib.asnn_device_read.argtypes = [vp, sz, vp, vp]
+    lib.asnn_device_gather.restype = ctypes.c_int
+    lib.asnn_device_gather.argtypes = [vp, i32, i32, i32, i32, u32, vp, vp]
     _lib = lib
     return lib
 
@@ -317,6 +322,25 @@ def asnn_device_copy(dst: torch.Tensor, src: torch.Tensor):
     rc = lib.asnn_device_copy(ctypes.c_void_p(dst.data_ptr()), ctypes.c_void_p(src.data_ptr()), nbytes, _stream())
     if rc != 0:
         raise AsnnError(rc, "asnn_device_copy")
+
+
+def asnn_device_read(src: torch.Tensor, sink: torch.Tensor):
+    """Streaming read of src on the current stream (bandwidth yardstick); sink: a device float."""
+    lib = load()
+    rc = lib.asnn_device_read(ctypes.c_void_p(src.data_ptr()), src.numel() * src.element_size(),
+                              ctypes.c_void_p(sink.data_ptr()), _stream())
+    if rc != 0:
+        raise AsnnError(rc, "asnn_device_read")
+
+
+def asnn_device_gather(buf: torch.Tensor, rows_per_launch: int, gathers: int, seed: int, sink: torch.Tensor):
+    """Random row gather over the float32 matrix buf in the launch shape of one level (bandwidth yardstick)."""
+    lib = load()
+    assert buf.dim() == 2 and buf.dtype == torch.float32 and buf.is_contiguous()
+    rc = lib.asnn_device_gather(ctypes.c_void_p(buf.data_ptr()), int(buf.shape[0]), int(buf.shape[1]), rows_per_launch,
+                                gathers, seed, ctypes.c_void_p(sink.data_ptr()), _stream())
+    if rc != 0:
+        raise AsnnError(rc, "asnn_device_gather")
 
 
 class Network:

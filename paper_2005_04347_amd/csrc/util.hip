@@ -1,6 +1,7 @@
-// asnn_device_copy: a plain streaming copy used as the bandwidth yardstick
-// (what fraction of a device copy the activation sustains) and as the kernel
-// of known traffic against which hardware byte counters are calibrated.
+// Bandwidth yardsticks: kernels of known traffic that do none of the method's arithmetic.  The
+// benchmark times them beside the activation (what a plain copy, a plain streaming read and a
+// random row gather of the activation's own shape sustain on this device), and the copy doubles
+// as the kernel of known traffic against which hardware byte counters are calibrated.
 #include "asnn_common.h"
 
 namespace asnn {
@@ -8,6 +9,63 @@ namespace {
 __global__ __launch_bounds__(256) void copy_kernel(const float4 *__restrict__ in, float4 *__restrict__ out, size_t n4) {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) out[i] = in[i];
+}
+
+// Streaming read: every thread keeps four 16-byte loads in flight and folds what it reads into one
+// number, which is stored only if it has a value that sums of ordinary data do not take (the store
+// keeps the loads alive without adding write traffic).
+__global__ __launch_bounds__(256) void read_kernel(const float4 *__restrict__ in, size_t n4, float *sink) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    float acc = 0.0f;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (; i + 3 * stride < n4; i += 4 * stride) {
+        const float4 a = in[i], b = in[i + stride], c = in[i + 2 * stride], d = in[i + 3 * stride];
+        acc += (a.x + a.y + a.z + a.w) + (b.x + b.y + b.z + b.w) + (c.x + c.y + c.z + c.w) + (d.x + d.y + d.z + d.w);
+    }
+    for (; i < n4; i += stride) {
+        const float4 a = in[i];
+        acc += a.x + a.y + a.z + a.w;
+    }
+    if (acc == -1.2345678e30f) sink[0] = acc;
+}
+
+__device__ inline uint32_t mix32(uint32_t x) {
+    x ^= x >> 15; x *= 0x2c1b3c6du; x ^= x >> 12; x *= 0x297a2d39u; x ^= x >> 15;
+    return x;
+}
+
+// Random row gather in the launch shape of a level of the activation: one single-wavefront block
+// per (row being computed, tile of batch columns), block index row-major, each wavefront loading
+// the same tile of `gathers` pseudo-random source rows (eight loads in flight), the 64 lanes
+// covering the tile with VEC floats each.  All tiles of one row pick the same source rows, as the
+// connections of a node do.  Only the additions that keep the loads alive are done.
+template <int VEC>
+__global__ __launch_bounds__(kWave) void gather_rows_kernel(const float *__restrict__ buf, uint32_t n_rows, int row_floats,
+                                                             int tiles, int gathers, uint32_t seed, float *sink) {
+    const uint32_t item_row = blockIdx.x / (uint32_t)tiles;
+    const int tile = (int)(blockIdx.x % (uint32_t)tiles);
+    const float *base = buf + (size_t)tile * (kWave * VEC) + threadIdx.x * VEC;
+    float acc = 0.0f;
+    for (int k0 = 0; k0 < gathers; k0 += 8) {
+        float v[8][VEC];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) v[k][j] = 0.0f;
+            if (k0 + k < gathers) {          // wave-uniform: the last round loads only what is left
+                const uint32_t h = mix32((item_row * 0x9e3779b1u) ^ ((uint32_t)(k0 + k) * 0x85ebca77u) ^ seed);
+                const uint32_t r = __umulhi(h, n_rows);
+                const float *p = base + (size_t)r * (size_t)row_floats;
+                if constexpr (VEC == 2) { const float2 t = *reinterpret_cast<const float2 *>(p); v[k][0] = t.x; v[k][1] = t.y; }
+                else { v[k][0] = *p; }
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) acc += v[k][j];
+    }
+    if (acc == -1.2345678e30f) sink[0] = acc;
 }
 }  // namespace
 }  // namespace asnn
@@ -20,6 +78,38 @@ extern "C" int asnn_device_copy(void *dst, const void *src, size_t bytes, void *
     const unsigned blocks = asnn::blocks_for(n4, 256 * 4, 256 * 32);
     hipLaunchKernelGGL(asnn::copy_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
                        static_cast<const float4 *>(src), static_cast<float4 *>(dst), n4);
+    ASNN_HIP_TRY(hipGetLastError());
+    return ASNN_OK;
+}
+
+extern "C" int asnn_device_read(const void *src, size_t bytes, float *sink, void *stream) {
+    if (!src || !sink) return ASNN_ERR_NULL;
+    if (bytes == 0) return ASNN_OK;
+    if ((bytes & 15u) != 0 || ((uintptr_t)src & 15u) != 0) return ASNN_ERR_SIZE;
+    const size_t n4 = bytes / 16;
+    const unsigned blocks = asnn::blocks_for(n4, 256 * 4, 256 * 32);
+    hipLaunchKernelGGL(asnn::read_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const float4 *>(src), n4, sink);
+    ASNN_HIP_TRY(hipGetLastError());
+    return ASNN_OK;
+}
+
+extern "C" int asnn_device_gather(const float *buf, int32_t n_rows, int32_t row_floats, int32_t rows_per_launch,
+                                  int32_t gathers, uint32_t seed, float *sink, void *stream) {
+    if (!buf || !sink) return ASNN_ERR_NULL;
+    if (n_rows <= 0 || row_floats <= 0 || rows_per_launch <= 0 || gathers <= 0) return ASNN_ERR_SIZE;
+    if (row_floats % asnn::kWave != 0 || ((uintptr_t)buf & 7u) != 0) return ASNN_ERR_SIZE;
+    const int vec = row_floats % (2 * asnn::kWave) == 0 ? 2 : 1;
+    const int tiles = row_floats / (asnn::kWave * vec);
+    const long long blocks = (long long)rows_per_launch * tiles;
+    if (blocks > 0x7fffffffLL) return ASNN_ERR_SIZE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (vec == 2)
+        hipLaunchKernelGGL(asnn::gather_rows_kernel<2>, dim3((unsigned)blocks), dim3(asnn::kWave), 0, s, buf, (uint32_t)n_rows,
+                           row_floats, tiles, gathers, seed, sink);
+    else
+        hipLaunchKernelGGL(asnn::gather_rows_kernel<1>, dim3((unsigned)blocks), dim3(asnn::kWave), 0, s, buf, (uint32_t)n_rows,
+                           row_floats, tiles, gathers, seed, sink);
     ASNN_HIP_TRY(hipGetLastError());
     return ASNN_OK;
 }

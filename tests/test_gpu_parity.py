@@ -547,6 +547,21 @@ def test_levels_across_narrow_and_wide_frontiers(amd, seed):
     assert e.value.code == -6
 
 
+def test_levels_of_a_very_deep_network(amd):
+    """4500 layers of one to three nodes behind two wide ones: the sweeps change from the grid-wide
+    kernel to the single workgroup that runs sweep after sweep on the device, whose count of sweeps is
+    only bounded by the network."""
+    rng = np.random.default_rng(4)
+    stages = [(3000, 0), (2500, 2)] + [(int(w), 2) for w in rng.integers(1, 4, size=4500)]
+    n, src, dst = _stages_network(stages, rng)
+    want, want_levels = oracle.levels(n, src, dst)
+    assert want_levels == len(stages) > 4096
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    got, n_levels = amd.asnn_build_levels(n, t(src), t(dst), t(np.zeros(0, np.int32)))
+    assert n_levels == want_levels
+    assert np.array_equal(got.cpu().numpy(), want)
+
+
 def _max_abs_err_every_element(V, inv, want, rows_per_chunk=1 << 18):
     """max |V[inv] - want| over EVERY element, in fp64 (exact for two floats), row chunk by row chunk
     so that the temporaries stay small next to a value matrix of a gigabyte.  V is the device result
