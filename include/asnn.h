@@ -208,7 +208,7 @@ int asnn_pack_csr(const int32_t *src, const int32_t *dst, const float *w, const 
  *     partial sums meet in the workspace and are added in chunk order.  A
  *     small launch ahead of it stages the sensors and marks every other row
  *     as not written; the copy to Y is done by the last work items of the
- *     persistent launch itself.  Needs the workspace and n_nodes*B*4 < 4 GiB;
+ *     persistent launch itself.  Needs the workspace;
  *   - workgroup: the shape of the paper's kernel, one workgroup walks all
  *     levels with a workgroup barrier between two levels; batch columns are
  *     independent, so there is one such workgroup per tile of up to 64

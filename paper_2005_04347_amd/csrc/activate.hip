@@ -415,18 +415,39 @@ struct DataflowCtl {
 };
 constexpr int kCtlMagic = 0x41534e4e;
 
+// Tiles of V travel with device scope (sc1) and 64-bit addresses: a value matrix may exceed the
+// 4 GiB that the 32-bit offsets of a buffer descriptor cover.  16 bytes per lane through the scoped
+// 128-bit global load / store, 8 and 4 bytes as relaxed atomics of that scope (the same instructions
+// with the sc1 bit).
+typedef __attribute__((address_space(1))) uintx4 *global_uintx4_ptr;
 template <int VEC>
-__device__ inline void load_vec_device_scope(__amdgpu_buffer_rsrc_t r, uint32_t byte_off, float (&out)[VEC]) {
-    if constexpr (VEC == 4) { floatx4 v = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, kAuxDeviceScope)); out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w; }
-    if constexpr (VEC == 2) { floatx2 v = __builtin_bit_cast(floatx2, __builtin_amdgcn_raw_buffer_load_b64(r, byte_off, 0, kAuxDeviceScope)); out[0] = v.x; out[1] = v.y; }
-    if constexpr (VEC == 1) { out[0] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, byte_off, 0, kAuxDeviceScope)); }
+__device__ inline void load_vec_device_scope(const float *p, float (&out)[VEC]) {
+    if constexpr (VEC == 4) {
+        const floatx4 v = __builtin_bit_cast(floatx4, __builtin_amdgcn_global_load_b128((global_uintx4_ptr)const_cast<float *>(p), "agent"));
+        out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+    }
+    if constexpr (VEC == 2) {
+        const floatx2 v = __builtin_bit_cast(floatx2, __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        out[0] = v.x; out[1] = v.y;
+    }
+    if constexpr (VEC == 1) {
+        out[0] = __builtin_bit_cast(float, __hip_atomic_load(reinterpret_cast<const unsigned int *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    }
 }
 
 template <int VEC>
-__device__ inline void store_vec_device_scope(__amdgpu_buffer_rsrc_t r, uint32_t byte_off, const float (&in)[VEC]) {
-    if constexpr (VEC == 4) { floatx4 v = {in[0], in[1], in[2], in[3]}; __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uintx4, v), r, byte_off, 0, kAuxDeviceScope); }
-    if constexpr (VEC == 2) { floatx2 v = {in[0], in[1]}; __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(uintx2, v), r, byte_off, 0, kAuxDeviceScope); }
-    if constexpr (VEC == 1) { __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, in[0]), r, byte_off, 0, kAuxDeviceScope); }
+__device__ inline void store_vec_device_scope(float *p, const float (&in)[VEC]) {
+    if constexpr (VEC == 4) {
+        const floatx4 v = {in[0], in[1], in[2], in[3]};
+        __builtin_amdgcn_global_store_b128((global_uintx4_ptr)p, __builtin_bit_cast(uintx4, v), "agent");
+    }
+    if constexpr (VEC == 2) {
+        const floatx2 v = {in[0], in[1]};
+        __hip_atomic_store(reinterpret_cast<unsigned long long *>(p), __builtin_bit_cast(unsigned long long, v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if constexpr (VEC == 1) {
+        __hip_atomic_store(reinterpret_cast<unsigned int *>(p), __builtin_bit_cast(unsigned int, in[0]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
 }
 
 // True when one of the values still holds the not-ready pattern.  Written as a minimum over
@@ -490,7 +511,7 @@ struct Patience {
 // first_row that still hold the not-ready pattern are read again.
 template <int VEC, int LPG, typename ACC, int U>
 __device__ inline void row_sum_dataflow(const int32_t *__restrict__ col, const float *__restrict__ w,
-                                        __amdgpu_buffer_rsrc_t vres, int B, int e_begin, int e_end, int c0, int first_row,
+                                        const float *V, int B, int e_begin, int e_end, int c0, int first_row,
                                         DataflowCtl *ctl, ACC (&acc)[VEC]) {
     constexpr int G = kWave / LPG;
     const int lane = threadIdx.x & (kWave - 1);
@@ -506,16 +527,16 @@ __device__ inline void row_sum_dataflow(const int32_t *__restrict__ col, const f
             for (int i = 0; i < n; i += U) {
                 float vals[U][VEC];
                 float ww[U];
-                uint32_t off[U];
+                const float *at[U];     // this lane's part of the source tile
                 bool watch[U];          // wave-uniform: a real connection whose source is above level 0
 #pragma unroll
                 for (int k = 0; k < U; ++k) {
                     const int idx = min(i + k, n - 1);
                     const int ck = __builtin_amdgcn_readlane(mc, idx);
                     ww[k] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, mw), idx));
-                    off[k] = ((uint32_t)ck * (uint32_t)B + (uint32_t)c0) * 4u;
+                    at[k] = V + (size_t)ck * (size_t)B + (size_t)c0;
                     watch[k] = (i + k < n) && ck >= first_row;
-                    load_vec_device_scope<VEC>(vres, off[k], vals[k]);
+                    load_vec_device_scope<VEC>(at[k], vals[k]);
                 }
                 for (;;) {      // look at every slot first, then request the missing tiles again (see below)
                     bool again[U];      // wave-uniform
@@ -528,7 +549,7 @@ __device__ inline void row_sum_dataflow(const int32_t *__restrict__ col, const f
                     if (!retry) break;
 #pragma unroll
                     for (int k = 0; k < U; ++k)
-                        if (again[k]) load_vec_device_scope<VEC>(vres, off[k], vals[k]);
+                        if (again[k]) load_vec_device_scope<VEC>(at[k], vals[k]);
                     if (!patience.again(ctl)) break;
                 }
 #pragma unroll
@@ -546,7 +567,7 @@ __device__ inline void row_sum_dataflow(const int32_t *__restrict__ col, const f
             for (int i = 0; i < n; i += G * UD) {
                 float vals[UD][VEC];
                 float ww[UD];
-                uint32_t off[UD];
+                const float *at[UD];
                 bool ok[UD], watch[UD];   // per lane group
 #pragma unroll
                 for (int k = 0; k < UD; ++k) {
@@ -555,9 +576,9 @@ __device__ inline void row_sum_dataflow(const int32_t *__restrict__ col, const f
                     const int sel = min(idx, n - 1);
                     const int ck = __shfl(mc, sel, kWave);
                     ww[k] = __shfl(mw, sel, kWave);
-                    off[k] = ((uint32_t)ck * (uint32_t)B + (uint32_t)c0) * 4u;
+                    at[k] = V + (size_t)ck * (size_t)B + (size_t)c0;
                     watch[k] = ok[k] && ck >= first_row;
-                    load_vec_device_scope<VEC>(vres, off[k], vals[k]);     // padded slots re-read a valid tile
+                    load_vec_device_scope<VEC>(at[k], vals[k]);     // padded slots re-read a valid tile
                 }
                 // All slots are looked at first (which takes every load of the last pass), then the
                 // tiles that are still missing are requested again back to back: measured 6 % faster on the
@@ -573,7 +594,7 @@ __device__ inline void row_sum_dataflow(const int32_t *__restrict__ col, const f
                     if (!__any(mine)) break;
 #pragma unroll
                     for (int k = 0; k < UD; ++k)
-                        if (again[k]) load_vec_device_scope<VEC>(vres, off[k], vals[k]);
+                        if (again[k]) load_vec_device_scope<VEC>(at[k], vals[k]);
                     if (!patience.again(ctl)) break;
                 }
 #pragma unroll
@@ -618,7 +639,7 @@ __host__ __device__ inline uint32_t partial_slot(int e_begin) { return (uint32_t
 template <int VEC, int LPG, typename ACC, int U>
 __global__ __launch_bounds__(kMixedBlock) void dataflow_kernel(const int32_t *__restrict__ row_ptr,
                                                                 const int32_t *__restrict__ col,
-                                                                const float *__restrict__ w, float *V, uint32_t v_bytes,
+                                                                const float *__restrict__ w, float *V,
                                                                 int B, const int32_t *__restrict__ unit_ptr,
                                                                 int first_unit, int n_work, int tiles, int first_row,
                                                                 DataflowCtl *ctl, void *partials, uint32_t partial_bytes,
@@ -631,7 +652,6 @@ __global__ __launch_bounds__(kMixedBlock) void dataflow_kernel(const int32_t *__
     __shared__ ACC part[kMixedWaves][T];
     __shared__ ACC others[kMaxHeavyChunks - 1][T];      // partial sums of the other chunks of a split row
     __shared__ int s_claim;
-    const __amdgpu_buffer_rsrc_t vres = __builtin_amdgcn_make_buffer_rsrc(V, 0, (int)v_bytes, kBufferFlags);
     const __amdgpu_buffer_rsrc_t pres = __builtin_amdgcn_make_buffer_rsrc(partials, 0, (int)partial_bytes, kBufferFlags);
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
     const int lane = threadIdx.x & (kWave - 1);
@@ -653,10 +673,10 @@ __global__ __launch_bounds__(kMixedBlock) void dataflow_kernel(const int32_t *__
                 float out[VEC];
                 if (id >= 0 && id < n_nodes) {
                     const int32_t row = inv_perm[id];
-                    const uint32_t off = ((uint32_t)row * (uint32_t)B + (uint32_t)c) * 4u;
+                    const float *at = V + (size_t)row * (size_t)B + (size_t)c;
                     Patience patience;
                     for (;;) {
-                        load_vec_device_scope<VEC>(vres, off, out);
+                        load_vec_device_scope<VEC>(at, out);
                         if (row < first_row || !shows_not_ready<VEC>(out) || !patience.again(ctl)) break;
                     }
                     // A wait that was given up anywhere leaves rows computed from unwritten sources:
@@ -704,7 +724,7 @@ __global__ __launch_bounds__(kMixedBlock) void dataflow_kernel(const int32_t *__
             }
             const int per = (e1 - e0 + share - 1) / share;
             const int b0 = min(e0 + slice * per, e1), b1 = min(b0 + per, e1);
-            row_sum_dataflow<VEC, LPG, ACC, U>(col, w, vres, B, b0, b1, active ? c : 0, first_row, ctl, acc);
+            row_sum_dataflow<VEC, LPG, ACC, U>(col, w, V, B, b0, b1, active ? c : 0, first_row, ctl, acc);
         } else {
 #pragma unroll
             for (int j = 0; j < VEC; ++j) acc[j] = ACC(0);
@@ -775,7 +795,7 @@ __global__ __launch_bounds__(kMixedBlock) void dataflow_kernel(const int32_t *__
                         float out[E];
 #pragma unroll
                         for (int j = 0; j < E; ++j) out[j] = squash(sum[j]);
-                        store_vec_device_scope<E>(vres, ((uint32_t)row * (uint32_t)B + ce) * 4u, out);
+                        store_vec_device_scope<E>(V + (size_t)row * (size_t)B + ce, out);
                     }
                 }
             }
@@ -789,13 +809,13 @@ __global__ __launch_bounds__(kMixedBlock) void dataflow_kernel(const int32_t *__
 #pragma unroll
                 for (int j = 1; j < VEC; ++j) mine = (gsel == j) ? acc[j] : mine;
                 const float out[1] = {squash(mine)};
-                store_vec_device_scope<1>(vres, ((uint32_t)row * (uint32_t)B + (uint32_t)(c + gsel)) * 4u, out);
+                store_vec_device_scope<1>(V + (size_t)row * (size_t)B + (size_t)(c + gsel), out);
             }
         } else if (active && lane < LPG) {               // light rows: one wavefront each
             float out[VEC];
 #pragma unroll
             for (int j = 0; j < VEC; ++j) out[j] = squash(acc[j]);
-            store_vec_device_scope<VEC>(vres, ((uint32_t)row * (uint32_t)B + (uint32_t)c) * 4u, out);
+            store_vec_device_scope<VEC>(V + (size_t)row * (size_t)B + (size_t)c, out);
         }
     }
 }
@@ -1227,7 +1247,6 @@ int launch_level_any(const LevelArgs &a, int hb, int mb, int lb, int le) {
 struct DataflowArgs {
     const int32_t *unit_ptr;
     int first_unit, n_work, first_row;
-    uint32_t v_bytes;
     DataflowCtl *ctl;
     int cus;
     int units_per_level;     // average, for sizing the persistent grid
@@ -1265,7 +1284,7 @@ int launch_dataflow(const LevelArgs &a, const DataflowArgs &d) {
     if (blocks > items) blocks = items;
     if (blocks < 1) return ASNN_OK;
     hipLaunchKernelGGL((dataflow_kernel<VEC, LPG, ACC, kUnroll>), dim3((unsigned)blocks), dim3(kMixedBlock), 0, a.s,
-                       a.row_ptr, a.col, a.w, a.V, d.v_bytes, a.B, d.unit_ptr, d.first_unit, d.n_work, tiles, d.first_row,
+                       a.row_ptr, a.col, a.w, a.V, a.B, d.unit_ptr, d.first_unit, d.n_work, tiles, d.first_row,
                        d.ctl, d.partials, d.partial_bytes, d.output_ids, d.inv_perm, d.Y, d.n_outputs, d.n_nodes);
     ASNN_HIP_TRY(hipGetLastError());
     return ASNN_OK;
@@ -1497,7 +1516,6 @@ int choose_schedule(const asnn_packed *packed, int32_t B, bool has_workspace, ui
     const bool possible = has_workspace && packed->unit_ptr && n_levels > 1 && packed->n_units > 0 &&
                           packed->first_unit >= 0 && packed->first_unit <= packed->n_units &&
                           n_work > 0 && n_work < 0x3fffffffLL &&
-                          (uint64_t)n_nodes * (uint64_t)B * 4u <= 0xffffffffull &&
                           carve_activate(nullptr, packed, B).partial_bytes <= 0xffffffffull;
     const bool workgroup_possible = packed->level_ptr != nullptr && tiles_for_workgroup(B) <= 0x7fffffffLL;
     if (flags & ASNN_FLAG_WORKGROUP) return workgroup_possible ? 2 : ASNN_ERR_NULL;
@@ -1690,8 +1708,7 @@ extern "C" int asnn_activate(const asnn_packed *packed, const int32_t *input_ids
         }
         ASNN_HIP_TRY(hipGetLastError());
         const int units_per_level = (packed->n_units - packed->first_unit + n_levels - 2) / (n_levels - 1);
-        DataflowArgs d{packed->unit_ptr, packed->first_unit, (int)n_work, first_row,
-                       (uint32_t)((uint64_t)n_nodes * (uint64_t)B * 4u), ws.ctl, cus, units_per_level,
+        DataflowArgs d{packed->unit_ptr, packed->first_unit, (int)n_work, first_row, ws.ctl, cus, units_per_level,
                        ws.partials, (uint32_t)ws.partial_bytes, output_ids, packed->inv_perm, Y,
                        (Y && n_outputs > 0) ? n_outputs : 0, n_nodes};
         ASNN_TRY(f32 ? launch_dataflow_any<float>(a, d) : launch_dataflow_any<double>(a, d));

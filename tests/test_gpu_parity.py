@@ -835,31 +835,30 @@ def test_teacher_forced_single_level_error(amd, idx):
 
 
 def test_value_matrix_beyond_4_gib(amd):
-    """n_nodes * B * 4 >= 4 GiB: the dataflow schedule addresses V with 32-bit byte offsets and must
-    not be taken (auto falls back to level launches, forcing it is refused); the other schedules
-    index with 64 bits.  Parity on sampled batch columns."""
+    """n_nodes * B * 4 >= 4 GiB: every schedule indexes the value matrix with 64 bits (the dataflow
+    schedule addresses its tiles through 64-bit global accesses of device scope, not through the
+    32-bit offsets of a buffer descriptor).  Parity on sampled batch columns, first, middle and
+    last rows written, for the default choice and every forced schedule."""
     wl = layered_skip(seed=5, n_nodes=1_100_000, n_inputs=64, n_outputs=64, n_levels=6, mean_extra_degree=1.0, B=8)
     B = 1024
     assert wl.n_nodes * B * 4 >= 1 << 32
     rng = np.random.default_rng(11)
     X = rng.random((len(wl.input_ids), B), dtype=np.float32)
     net = amd.Network(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.output_ids)
-    assert amd.asnn_activate_schedule(net.graph, B, True, 0) == "levels"
-    with pytest.raises(amd.AsnnError) as e:
-        amd.asnn_activate_schedule(net.graph, B, True, DATAFLOW)
-    assert e.value.code == -2
+    assert amd.asnn_activate_schedule(net.graph, B, True, DATAFLOW) == "dataflow"
     cols = np.array([0, 511, 1023])
     want = oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, np.ascontiguousarray(X[:, cols]))
     inv = net.graph.inv_perm.long()
     tcols = torch.as_tensor(cols, device="cuda:0")
-    for sched in (0, WORKGROUP):
+    for sched in (0, LEVELS, DATAFLOW, WORKGROUP):
         V = torch.full((wl.n_nodes, B), float("nan"), device="cuda:0")
         V, Y = net.activate(X, V=V, flags=sched)
-        torch.cuda.synchronize()
+        net.check(B)
         got = V[:, tcols][inv].cpu().numpy()
         err = float(np.abs(got.astype(np.float64) - want).max())
         assert err <= TIGHT, (sched, err)
-        assert not torch.isnan(V[-1]).any() and not torch.isnan(V[wl.n_nodes // 2]).any()
+        assert not torch.isnan(V[-1]).any() and not torch.isnan(V[wl.n_nodes // 2]).any() and not torch.isnan(V[0]).any()
+        assert torch.equal(Y, V[inv[net.output_ids.long()]]), sched
         del V, Y
 
 
