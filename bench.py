@@ -74,10 +74,18 @@ def measured_traffic(config, flags):
     return traffic if sha == kernel_source_sha256() else None
 
 
-def paper_regime(flags=0):
+def paper_regime(flags=0, quick=False):
     """The paper's own experiment on this machine: ONE input vector per activation, time against the
     number of connections for shallow and deep networks, GPU (10 runs averaged, as in the paper's
-    experimental setup) against the sequential oracle (5 runs averaged).  Prints one JSON line per network."""
+    experimental setup) against the sequential oracle (5 runs averaged).  Prints one JSON line per network.
+
+    GPU figures, all with the network resident: "resident" = 10 activations enqueued back to back through
+    a call whose arguments were marshalled once (Network.bind), between two events; "graph replay" = the
+    same 10 activations captured in a HIP graph and replayed (no host call between two kernels: what the
+    device itself needs per activation, kernel plus hand-over); "binding" = the same through the general
+    Python entry point, which marshals thirteen arguments and looks the stream up on every call; "with
+    host copies" = host X in, host Y out around every activation, as the paper timed it; "pinned I/O" =
+    X and Y in pinned host memory that the kernels read and write in place."""
     import numpy as np
     import torch
 
@@ -90,6 +98,18 @@ def paper_regime(flags=0):
     # connections swept at two depths, then depth swept at a fixed number of connections
     sweep = [(L, E) for L in (5, 40) for E in (1000, 2000, 4000, 8000, 16000, 30000, 70000, 150000, 300000)]
     sweep += [(L, 16000) for L in (3, 10, 20, 80, 160)]
+    if quick:
+        sweep = [(5, 1000), (5, 16000), (40, 4000)]
+
+    def events_around(fn, reps=10):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps
+
     for index, (n_levels, n_edges) in enumerate(sweep[:1] + sweep):     # the first network once more, unreported: first-use costs
         n_nodes = max(n_edges // 10, 3 * n_levels)
         n_io = max(4, n_nodes // 50)
@@ -99,17 +119,26 @@ def paper_regime(flags=0):
         X = torch.from_numpy(wl.X).cuda()
         V = torch.empty((wl.n_nodes, 1), device="cuda")
         Y = torch.empty((len(wl.output_ids), 1), device="cuda")
+        bound = net.bind(X, V=V, Y=Y, flags=flags)
         for _ in range(5):
-            net.activate(X, V=V, Y=Y, flags=flags)
+            bound.launch()
         torch.cuda.synchronize()
-        # resident: events around 10 activations; with transfers: host X in, host Y out, as the paper timed it
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(10):
-            net.activate(X, V=V, Y=Y, flags=flags)
-        e1.record()
+        gpu_us = min(events_around(bound.launch) for _ in range(3))
+        binding_us = min(events_around(lambda: net.activate(X, V=V, Y=Y, flags=flags)) for _ in range(3))
+        # ten activations in one HIP graph (captured on a side stream), replayed
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            side_bound = net.bind(X, V=V, Y=Y, flags=flags)
+            side_bound.launch()
+            side.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                for _ in range(10):
+                    side_bound.launch()
         torch.cuda.synchronize()
-        gpu_us = e0.elapsed_time(e1) * 1e3 / 10
+        graph.replay()
+        torch.cuda.synchronize()
+        graph_us = min(events_around(graph.replay, reps=3) for _ in range(3)) / 10
         t0 = time.perf_counter()
         for _ in range(10):
             Xd = torch.from_numpy(wl.X).cuda()
@@ -120,14 +149,14 @@ def paper_regime(flags=0):
         Xp = torch.empty(wl.X.shape, dtype=torch.float32, pin_memory=True)
         Yp = torch.empty((len(wl.output_ids), 1), dtype=torch.float32, pin_memory=True)
         x_host = torch.from_numpy(wl.X)
-        ws = net.workspace(1)
+        pinned = net.bind(Xp, V=V, Y=Yp, flags=flags)
         for _ in range(5):
-            amd.asnn_activate(net.graph, net.input_ids, Xp, net.output_ids, V=V, Y=Yp, flags=flags, workspace=ws)
+            pinned.launch()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(10):
             Xp.copy_(x_host)
-            amd.asnn_activate(net.graph, net.input_ids, Xp, net.output_ids, V=V, Y=Yp, flags=flags, workspace=ws)
+            pinned.launch()
             torch.cuda.synchronize()
             y_host = Yp.clone()
         pinned_us = (time.perf_counter() - t0) * 1e6 / 10
@@ -144,7 +173,8 @@ def paper_regime(flags=0):
         print(json.dumps({"regime": "paper: batch 1", "connections": wl.n_edges, "nodes": wl.n_nodes,
                           "levels": net.n_levels,
                           "schedule_taken": amd.asnn_activate_schedule(net.graph, 1, True, flags),
-                          "gpu_us_resident": round(gpu_us, 1),
+                          "gpu_us_resident": round(gpu_us, 1), "gpu_us_graph_replay": round(graph_us, 1),
+                          "gpu_us_resident_through_binding": round(binding_us, 1),
                           "gpu_us_with_host_copies": round(copy_us, 1),
                           "gpu_us_pinned_host_io": round(pinned_us, 1), "cpu_oracle_us": round(cpu_us, 1),
                           "speedup_resident": round(cpu_us / gpu_us, 2),
@@ -163,11 +193,12 @@ def main():
                     help="level launches, persistent dataflow launch, or the library's own choice")
     ap.add_argument("--graph", action="store_true", help="capture one asnn_activate in a HIP graph and time replays")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--regime-quick", action="store_true", help="with --paper-regime: three networks only (for profiling)")
     ap.add_argument("--paper-regime", action="store_true",
                     help="batch-1 latency against connections, as in the paper's figures (prints one line per network)")
     args = ap.parse_args()
     if args.paper_regime:
-        paper_regime({"auto": 0, "levels": 4, "dataflow": 8, "workgroup": 16}[args.schedule])
+        paper_regime({"auto": 0, "levels": 4, "dataflow": 8, "workgroup": 16}[args.schedule], quick=args.regime_quick)
         return
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (batch columns and networks of a population would shard "

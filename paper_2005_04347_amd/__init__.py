@@ -6,6 +6,7 @@ binding above it; build the library with ``python -m paper_2005_04347_amd.build`
 """
 from .binding import (  # noqa: F401
     AsnnError,
+    BoundActivation,
     FLAG_ACC_F32,
     FLAG_DATAFLOW,
     FLAG_LEVEL_LAUNCHES,

@@ -274,6 +274,37 @@ def asnn_activate(g: PackedGraph, input_ids: torch.Tensor, X: torch.Tensor,
     return V, Y
 
 
+class BoundActivation:
+    """One asnn_activate call with every argument marshalled once: launch() only makes the foreign
+    call.  For loops that activate the same network on the same buffers again and again (one input
+    vector per activation: there the marshalling of thirteen arguments and the look-up of the
+    current stream cost more than the kernel).  The stream is the one that was current when the
+    object was made; X, V, Y and the workspace are kept alive by it."""
+
+    def __init__(self, g: PackedGraph, input_ids, X, output_ids, V, Y, flags, workspace):
+        lib = load()
+        assert X.dim() == 2 and X.dtype == torch.float32 and X.is_contiguous()
+        B = int(X.shape[1])
+        n_in = int(input_ids.numel())
+        assert X.shape[0] == n_in
+        assert V.shape == (g.n_nodes, B) and V.is_contiguous() and V.dtype == torch.float32
+        n_out = 0 if output_ids is None else int(output_ids.numel())
+        assert n_out == 0 or (Y is not None and Y.shape == (n_out, B) and Y.is_contiguous())
+        self._keep = (g, input_ids, X, output_ids, V, Y, workspace)
+        self._fn = lib.asnn_activate
+        self._args = (ctypes.byref(g.record), _ptr(input_ids), ctypes.c_int32(n_in), _ptr(output_ids), ctypes.c_int32(n_out),
+                      _ptr(X), ctypes.c_int32(B), ctypes.c_void_p(V.data_ptr()), _ptr(Y),
+                      None if workspace is None else ctypes.c_void_p(workspace.data_ptr()),
+                      ctypes.c_size_t(0 if workspace is None else workspace.numel() * workspace.element_size()),
+                      ctypes.c_uint32(flags), _stream())
+        self.V, self.Y = V, Y
+
+    def launch(self) -> None:
+        rc = self._fn(*self._args)
+        if rc != 0:
+            raise AsnnError(rc, "asnn_activate")
+
+
 def asnn_activate_static(g: PackedGraph, input_ids: torch.Tensor, X: torch.Tensor, V: torch.Tensor,
                          output_ids: Optional[torch.Tensor] = None, Y: Optional[torch.Tensor] = None, flags: int = 0):
     """asnn_activate with the library's own scratch in the place of a workspace.  The binding allocates
@@ -380,6 +411,20 @@ class Network:
             if check:
                 asnn_activate_status(ws)
             return out
+
+    def bind(self, X: torch.Tensor, V: Optional[torch.Tensor] = None, Y: Optional[torch.Tensor] = None,
+             flags: int = 0, use_workspace: bool = True) -> BoundActivation:
+        """Marshals one activation of this network once; the returned object's launch() enqueues it on the
+        stream that is current now, reading X and writing V and Y in place every time."""
+        assert X.is_cuda or X.is_pinned()
+        B = int(X.shape[1])
+        with torch.cuda.device(self.device):
+            if V is None:
+                V = torch.empty((self.n_nodes, B), dtype=torch.float32, device=self.device)
+            if Y is None:
+                Y = torch.empty((int(self.output_ids.numel()), B), dtype=torch.float32, device=self.device)
+            ws = self.workspace(B) if use_workspace else None
+            return BoundActivation(self.graph, self.input_ids, X, self.output_ids, V, Y, flags, ws)
 
     def check(self, B: int) -> None:
         """Synchronises and raises if the last dataflow activation at batch B timed out."""

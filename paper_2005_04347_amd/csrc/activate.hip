@@ -903,9 +903,45 @@ __global__ __launch_bounds__(kMixedBlock) void workgroup_kernel(
     const float *Vr = STAGED ? s_V : V;
     const int ld = STAGED ? T : B;                     // row stride of Vr
     const int cr = STAGED ? ct : (col_ok ? c : 0);     // this lane's first column in Vr
+    // The first sensor and the first output row of this lane group are looked up now, beside the
+    // staging loads, and kept in registers: two chains of dependent loads (id -> packed row -> value)
+    // that would otherwise stand alone after a barrier each, a few microseconds of an activation
+    // that takes five.  (Further sensors and outputs of the group, beyond kSlots of either, are
+    // looked up where they are needed.)
+    int32_t first_in_row = -1, first_out_row = -1;
+    float first_x[VEC];
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) first_x[j] = 0.0f;
+    if (slot < n_inputs) {
+        const int32_t id = input_ids[slot];
+        if (col_ok) {
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) first_x[j] = X[(size_t)slot * (size_t)B + c + j];
+        }
+        if (id >= 0 && id < n_nodes) first_in_row = inv_perm[id];
+    }
+    if (Y != nullptr && slot < n_outputs) {
+        const int32_t id = output_ids[slot];
+        if (id >= 0 && id < n_nodes) first_out_row = inv_perm[id];
+    }
     if constexpr (STAGED == 2) {
         for (int i = threadIdx.x; i <= n_nodes; i += kMixedBlock) s_row_ptr[i] = row_ptr[i];
-        for (int i = threadIdx.x; i < n_edges; i += kMixedBlock) { s_col[i] = col[i]; s_w[i] = w[i]; }
+        // eight connections per thread and round, all their loads in flight before the first LDS store
+        for (int i0 = threadIdx.x; i0 < n_edges; i0 += 8 * kMixedBlock) {
+            int32_t cc[8];
+            float ww[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int i = min(i0 + k * kMixedBlock, n_edges - 1);
+                cc[k] = col[i];
+                ww[k] = w[i];
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int i = i0 + k * kMixedBlock;
+                if (i < n_edges) { s_col[i] = cc[k]; s_w[i] = ww[k]; }
+            }
+        }
         for (int i = threadIdx.x; i <= ASNN_CLASSES * n_levels; i += kMixedBlock) s_level_ptr[i] = level_ptr[i];
         __syncthreads();
     }
@@ -941,7 +977,13 @@ __global__ __launch_bounds__(kMixedBlock) void workgroup_kernel(
         for (int r = slot; r < level0_end; r += kSlots) put(r, half);
     }
     __syncthreads();
-    for (int k = slot; k < n_inputs; k += kSlots) {
+    if (first_in_row >= 0) {
+        float out[VEC];
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) out[j] = raw ? first_x[j] : squash((ACC)first_x[j]);
+        put(first_in_row, out);
+    }
+    for (int k = slot + kSlots; k < n_inputs; k += kSlots) {
         const int32_t id = input_ids[k];
         if (id < 0 || id >= n_nodes) continue;
         float out[VEC];
@@ -1086,7 +1128,14 @@ __global__ __launch_bounds__(kMixedBlock) void workgroup_kernel(
     }
 
     if (Y != nullptr && col_ok) {
-        for (int o = slot; o < n_outputs; o += kSlots) {
+        if (slot < n_outputs) {
+            const bool ok = first_out_row >= 0;
+            const size_t row = ok ? (size_t)first_out_row : 0;
+#pragma unroll
+            for (int j = 0; j < VEC; ++j)
+                Y[(size_t)slot * (size_t)B + c + j] = ok ? Vr[row * (size_t)ld + cr + j] : __builtin_nanf("");
+        }
+        for (int o = slot + kSlots; o < n_outputs; o += kSlots) {
             const int32_t id = output_ids[o];
             const bool ok = id >= 0 && id < n_nodes;
             const size_t row = ok ? (size_t)inv_perm[id] : 0;
