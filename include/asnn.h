@@ -48,8 +48,9 @@
  *   - the default arithmetic is the one that meets the parity bar on every
  *     workload (fp64 sums and sigmoid, one rounding to float);
  *     ASNN_FLAG_ACC_F32 selects float arithmetic, not the other way round;
- *   - results restricted to the required set R are obtained by filtering the
- *     connections beforehand (asnn_required_set / asnn_filter_required) rather
+ *   - results restricted to the required set R are obtained by filtering (and,
+ *     for a value matrix of |R| rows, compacting) the network beforehand
+ *     (asnn_required_set / asnn_filter_required / asnn_compact_required) rather
  *     than by a flag of asnn_activate;
  *   - the library keeps no cache of graphs or launches between calls, so there
  *     is nothing to clear: every buffer, workspaces included, is the caller's.
@@ -144,6 +145,29 @@ int asnn_filter_required(int32_t n_nodes, int64_t n_edges, const int32_t *src, c
                          const int32_t *required,
                          int32_t *src_out, int32_t *dst_out, float *w_out, int64_t *n_kept_out,
                          void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---- 1c. outputs-only networks (optional) -----------------------------------
+ * After asnn_required_set / asnn_filter_required the nodes outside R still
+ * occupy rows of the value matrix.  asnn_compact_required numbers the nodes of
+ * R densely (0 .. |R|-1, in the order of their old ids) and asnn_relabel_ids
+ * carries id lists over to that numbering, so that the network can be built,
+ * packed and activated on |R| nodes: nothing outside R is allocated, written
+ * or read, and V is |R| x B.  A connection kept by asnn_filter_required has
+ * both ends in R.  An id outside R (a sensor no output depends on) becomes -1,
+ * which asnn_activate skips, so X keeps its rows.
+ *   required     device int32[n_nodes]   from asnn_required_set
+ *   new_id_out   device int32[n_nodes]   dense id, or -1 outside R
+ *   n_required_out host int32*           |R|
+ *   workspace    device, >= asnn_compact_workspace_bytes(n_nodes), 256-byte aligned
+ *   ids, ids_out device int32[n_ids]     (asnn_relabel_ids; may be the same array;
+ *                ids outside [0,n_nodes) become -1)
+ * Errors: NULL, SIZE, WORKSPACE, HIP.  asnn_compact_required blocks until the
+ * count is known; asnn_relabel_ids is asynchronous. */
+size_t asnn_compact_workspace_bytes(int32_t n_nodes);
+int asnn_compact_required(int32_t n_nodes, const int32_t *required, int32_t *new_id_out,
+                          int32_t *n_required_out, void *workspace, size_t workspace_bytes, void *stream);
+int asnn_relabel_ids(const int32_t *ids, int64_t n_ids, const int32_t *new_id, int32_t n_nodes,
+                     int32_t *ids_out, void *stream);
 
 /* ---- 2. pack -----------------------------------------------------------
  * Level-contiguous, destination-sorted CSR (replaces the paper's per-node

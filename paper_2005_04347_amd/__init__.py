@@ -27,7 +27,9 @@ from .binding import (  # noqa: F401
     asnn_device_copy,
     asnn_device_gather,
     asnn_device_read,
+    asnn_compact_required,
     asnn_filter_required,
+    asnn_relabel_ids,
     asnn_required_set,
     asnn_pack_csr,
     load,

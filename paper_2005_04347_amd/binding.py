@@ -38,6 +38,7 @@ EXPORTS = [
     "asnn_strerror", "asnn_last_hip_error", "asnn_version",
     "asnn_levels_workspace_bytes", "asnn_build_levels",
     "asnn_required_workspace_bytes", "asnn_required_set", "asnn_filter_workspace_bytes", "asnn_filter_required",
+    "asnn_compact_workspace_bytes", "asnn_compact_required", "asnn_relabel_ids",
     "asnn_pack_workspace_bytes", "asnn_pack_csr", "asnn_activate_workspace_bytes", "asnn_activate",
     "asnn_activate_status", "asnn_activate_schedule", "asnn_activate_static", "asnn_device_copy",
     "asnn_device_read", "asnn_device_gather",
@@ -84,6 +85,12 @@ def load() -> ctypes.CDLL:
     lib.asnn_filter_workspace_bytes.argtypes = [i64]
     lib.asnn_filter_required.restype = ctypes.c_int
     lib.asnn_filter_required.argtypes = [i32, i64, vp, vp, vp, vp, vp, vp, vp, ctypes.POINTER(i64), vp, sz, vp]
+    lib.asnn_compact_workspace_bytes.restype = sz
+    lib.asnn_compact_workspace_bytes.argtypes = [i32]
+    lib.asnn_compact_required.restype = ctypes.c_int
+    lib.asnn_compact_required.argtypes = [i32, vp, vp, ctypes.POINTER(i32), vp, sz, vp]
+    lib.asnn_relabel_ids.restype = ctypes.c_int
+    lib.asnn_relabel_ids.argtypes = [vp, i64, vp, i32, vp, vp]
     lib.asnn_pack_workspace_bytes.restype = sz
     lib.asnn_pack_workspace_bytes.argtypes = [i32, i64]
     lib.asnn_pack_csr.restype = ctypes.c_int
@@ -184,6 +191,30 @@ def asnn_filter_required(n_nodes: int, src, dst, w, required):
         raise AsnnError(rc, "asnn_filter_required")
     k = int(kept.value)
     return so[:k], do[:k], wo[:k]
+
+
+def asnn_compact_required(n_nodes: int, required: torch.Tensor):
+    """-> (new_id: int32 device tensor [n_nodes], dense id of every node of R or -1; n_required: int)."""
+    lib = load()
+    device = required.device
+    new_id = torch.empty(max(n_nodes, 1), dtype=torch.int32, device=device)
+    ws = _workspace(lib.asnn_compact_workspace_bytes(n_nodes), device)
+    count = ctypes.c_int32(-1)
+    rc = lib.asnn_compact_required(n_nodes, _ptr(required), ctypes.c_void_p(new_id.data_ptr()), ctypes.byref(count),
+                                   ctypes.c_void_p(ws.data_ptr()), ws.numel(), _stream())
+    if rc != 0:
+        raise AsnnError(rc, "asnn_compact_required")
+    return new_id[:n_nodes], int(count.value)
+
+
+def asnn_relabel_ids(ids: torch.Tensor, new_id: torch.Tensor) -> torch.Tensor:
+    """ids carried over to the numbering new_id (from asnn_compact_required); -1 where an id is outside R."""
+    lib = load()
+    out = torch.empty_like(ids)
+    rc = lib.asnn_relabel_ids(_ptr(ids), int(ids.numel()), _ptr(new_id), int(new_id.numel()), _ptr(out), _stream())
+    if rc != 0:
+        raise AsnnError(rc, "asnn_relabel_ids")
+    return out
 
 
 class AsnnPacked(ctypes.Structure):
@@ -377,7 +408,10 @@ def asnn_device_gather(buf: torch.Tensor, rows_per_launch: int, gathers: int, se
 class Network:
     """Convenience wrapper: build levels + pack once, activate many times."""
 
-    def __init__(self, n_nodes, src, dst, w, input_ids, output_ids, device="cuda:0", required_only=False):
+    def __init__(self, n_nodes, src, dst, w, input_ids, output_ids, device="cuda:0", required_only=False, compact=False):
+        """required_only: drop the connections no output depends on (same rows of V, bit-identical on R).
+        compact: also drop the nodes no output depends on: the network is renumbered (self.new_id), V has
+        |R| rows and nothing outside R is allocated or written."""
         self.device = torch.device(device)
         self.n_nodes = int(n_nodes)
         self.src = _dev_i32(src, self.device)
@@ -386,12 +420,22 @@ class Network:
         self.input_ids = _dev_i32(input_ids, self.device)
         self.output_ids = _dev_i32(output_ids, self.device)
         self.required = None
+        self.new_id = None           # compact=True: original id -> id in the compacted network, -1 outside R
         with torch.cuda.device(self.device):
-            if required_only:       # keep only the connections the outputs depend on
+            if required_only or compact:       # keep only the connections the outputs depend on
                 self.required, self.n_required = asnn_required_set(self.n_nodes, self.src, self.dst, self.output_ids)
                 self.src, self.dst, self.w_edges = asnn_filter_required(self.n_nodes, self.src, self.dst, self.w_edges,
                                                                         self.required)
-            self.level, self.n_levels = asnn_build_levels(self.n_nodes, self.src, self.dst, self.input_ids)
+            if compact:                        # and number the required nodes densely: V has |R| rows
+                self.new_id, count = asnn_compact_required(self.n_nodes, self.required)
+                self.src = asnn_relabel_ids(self.src, self.new_id)
+                self.dst = asnn_relabel_ids(self.dst, self.new_id)
+                self.input_ids = asnn_relabel_ids(self.input_ids, self.new_id)     # -1: a sensor no output depends on (skipped)
+                self.output_ids = asnn_relabel_ids(self.output_ids, self.new_id)
+                self.n_nodes_original, self.n_nodes = self.n_nodes, count
+                self.sensor_ids = self.input_ids[self.input_ids >= 0]              # what the level builder may be told
+            self.level, self.n_levels = asnn_build_levels(self.n_nodes, self.src, self.dst,
+                                                          self.sensor_ids if compact else self.input_ids)
             self.graph = asnn_pack_csr(self.n_nodes, self.n_levels, self.src, self.dst, self.w_edges, self.level)
 
         self._workspaces = {}

@@ -616,6 +616,31 @@ __global__ void compact_edges_kernel(const int32_t *__restrict__ src, const int3
     }
 }
 
+// Compaction to the required set: nodes of R get the dense ids 0 .. |R|-1 in the order of their
+// old ids (pos = exclusive prefix sum of the required flags), everything else gets -1.
+__global__ void new_id_kernel(const int32_t *__restrict__ required, const int32_t *__restrict__ pos, int32_t n_nodes,
+                              int32_t *__restrict__ new_id) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < n_nodes; v += stride)
+        new_id[v] = required[v] != 0 ? pos[v] : -1;
+}
+
+__global__ void required_flag_kernel(const int32_t *__restrict__ required, int32_t n_nodes, int32_t *__restrict__ flag) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v <= n_nodes; v += stride)
+        flag[v] = (v < n_nodes && required[v] != 0) ? 1 : 0;
+}
+
+// ids[k] -> new_id[ids[k]] (-1 for an id out of range or outside R)
+__global__ void relabel_kernel(const int32_t *__restrict__ ids, int64_t n, const int32_t *__restrict__ new_id,
+                               int32_t n_nodes, int32_t *__restrict__ out) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; k < n; k += stride) {
+        const int32_t v = ids[k];
+        out[k] = (v >= 0 && v < n_nodes) ? new_id[v] : -1;
+    }
+}
+
 struct FilterWorkspace {
     int *err;
     int32_t *pos, *scan_tmp;
@@ -712,4 +737,41 @@ extern "C" int asnn_filter_required(int32_t n_nodes, int64_t n_edges, const int3
     ASNN_HIP_TRY(hipStreamSynchronize(s));
     *n_kept_out = kept;
     return host_err;
+}
+
+extern "C" size_t asnn_compact_workspace_bytes(int32_t n_nodes) {
+    if (n_nodes < 0) return 0;
+    return carve_filter(nullptr, (int64_t)n_nodes).bytes;
+}
+
+extern "C" int asnn_compact_required(int32_t n_nodes, const int32_t *required, int32_t *new_id_out,
+                                     int32_t *n_required_out, void *workspace, size_t workspace_bytes, void *stream) {
+    if (n_nodes <= 0) return ASNN_ERR_SIZE;
+    if (!required || !new_id_out || !n_required_out || !workspace) return ASNN_ERR_NULL;
+    if (((uintptr_t)workspace & 255u) != 0 || workspace_bytes < asnn_compact_workspace_bytes(n_nodes))
+        return ASNN_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    FilterWorkspace ws = carve_filter(workspace, (int64_t)n_nodes);
+    const unsigned nb = blocks_for((size_t)n_nodes + 1, kThreads, 65535);
+    hipLaunchKernelGGL(required_flag_kernel, dim3(nb), dim3(kThreads), 0, s, required, n_nodes, ws.pos);
+    ASNN_HIP_TRY(hipGetLastError());
+    ASNN_TRY(exclusive_scan_i32(ws.pos, ws.pos, (size_t)n_nodes + 1, ws.scan_tmp, s));
+    hipLaunchKernelGGL(new_id_kernel, dim3(nb), dim3(kThreads), 0, s, required, (const int32_t *)ws.pos, n_nodes, new_id_out);
+    ASNN_HIP_TRY(hipGetLastError());
+    int32_t count = 0;
+    ASNN_HIP_TRY(hipMemcpyAsync(&count, ws.pos + n_nodes, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    ASNN_HIP_TRY(hipStreamSynchronize(s));
+    *n_required_out = count;
+    return ASNN_OK;
+}
+
+extern "C" int asnn_relabel_ids(const int32_t *ids, int64_t n_ids, const int32_t *new_id, int32_t n_nodes,
+                                int32_t *ids_out, void *stream) {
+    if (n_ids < 0 || n_nodes <= 0) return ASNN_ERR_SIZE;
+    if (n_ids == 0) return ASNN_OK;
+    if (!ids || !new_id || !ids_out) return ASNN_ERR_NULL;
+    hipLaunchKernelGGL(relabel_kernel, dim3(blocks_for((size_t)n_ids, kThreads, 65535)), dim3(kThreads), 0,
+                       static_cast<hipStream_t>(stream), ids, n_ids, new_id, n_nodes, ids_out);
+    ASNN_HIP_TRY(hipGetLastError());
+    return ASNN_OK;
 }

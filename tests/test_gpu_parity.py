@@ -811,6 +811,42 @@ def test_required_set_and_filtered_activation(amd, idx, scale):
     assert e.value.code == -3
 
 
+@pytest.mark.parametrize("idx,scale,n_outputs", [(1, "full", 2), (3, "small", 3), (4, "small", 2), (3, "full", 5)])
+def test_compacted_required_network(amd, idx, scale, n_outputs):
+    """Outputs-only activation: the network restricted to the required set R and renumbered densely.
+    The value matrix has |R| rows (nothing outside R is allocated or written), every node of R gets
+    the oracle's value of the full network, and Y equals the full network's Y.  Few outputs, so that R
+    leaves a good part of the network out; a sensor outside R is skipped."""
+    wl = make_config(idx, scale)
+    outs = wl.output_ids[:n_outputs]
+    want_R = oracle.required(wl.n_nodes, wl.src, wl.dst, outs)
+    assert 0 < want_R.sum() < wl.n_nodes
+    want = oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.X)
+    full = amd.Network(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, outs)
+    cut = amd.Network(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, outs, compact=True)
+    n_R = int(want_R.sum())
+    assert cut.n_nodes == n_R and cut.n_required == n_R and cut.n_nodes_original == wl.n_nodes
+    new_id = cut.new_id.cpu().numpy()
+    assert ((new_id >= 0) == want_R).all()
+    assert (new_id[want_R] == np.arange(n_R)).all()                   # dense, in the order of the old ids
+    assert (cut.input_ids.cpu().numpy() == new_id[wl.input_ids]).all()
+    # the compacted network's levels are the full network's levels of the same nodes
+    lv, _ = oracle.levels(wl.n_nodes, wl.src, wl.dst)
+    assert (cut.level.cpu().numpy() == lv[want_R]).all()
+    for sched in (0, LEVELS, DATAFLOW, WORKGROUP):
+        V = torch.full((n_R, wl.B), float("nan"), device="cuda:0")
+        V, Y = cut.activate(wl.X, V=V, flags=sched)
+        cut.check(wl.B)
+        assert V.shape == (n_R, wl.B)
+        got = cut.values_original_order(V).cpu().numpy()               # indexed by the compacted ids
+        err = float(np.abs(got.astype(np.float64) - want[want_R]).max())
+        assert err <= TIGHT, (sched, err)
+        Vf, Yf = full.activate(wl.X, flags=sched)
+        full.check(wl.B)
+        assert np.abs(Y.cpu().numpy().astype(np.float64) - Yf.cpu().numpy()).max() <= TIGHT, sched
+        assert (Y.cpu().numpy() == got[new_id[outs]]).all(), sched
+
+
 @pytest.mark.parametrize("idx", [3, 4, 5])
 def test_teacher_forced_single_level_error(amd, idx):
     """Every node computed from the ORACLE's values of its sources (one hop), so the error of one
