@@ -111,3 +111,36 @@ def test_static_scratch_refuses_what_does_not_fit(amd):
     torch.cuda.synchronize()
     assert torch.isnan(V).all() and torch.isnan(Y).all()          # nothing ran
     # (a batch that fits runs: covered by the test above)
+
+
+def test_static_scratch_under_graph_capture(amd):
+    """The callers the entry point is for: asnn_activate_static captured in a HIP graph (it enqueues
+    kernels only), replayed several times with eager work between the replays, every replay equal to
+    the eager result; the dataflow schedule with split rows, whose scratch is the library's own."""
+    wl = _split_rows_network(5, n_in=200, n_mid=30, degrees=[4, 50, 700, 2500], B=16)
+    net = amd.Network(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.output_ids)
+    X = torch.from_numpy(wl.X).cuda()
+    want_V, want_Y = net.activate(X, flags=DATAFLOW)
+    net.check(wl.B)
+    V = torch.zeros_like(want_V)
+    Y = torch.zeros_like(want_Y)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        amd.asnn_activate_static(net.graph, net.input_ids, X, V, net.output_ids, Y, flags=DATAFLOW)      # warm-up on the capture stream
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            amd.asnn_activate_static(net.graph, net.input_ids, X, V, net.output_ids, Y, flags=DATAFLOW)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        V.fill_(float("nan"))
+        Y.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(V, want_V) and torch.equal(Y, want_Y), rep
+        other = _split_rows_network(6 + rep, n_in=50, n_mid=10, degrees=[3, 600], B=3)       # eager work on the same scratch between replays
+        onet = amd.Network(other.n_nodes, other.src, other.dst, other.w, other.input_ids, other.output_ids)
+        oV = torch.empty((other.n_nodes, 3), device="cuda:0")
+        oY = torch.empty((len(other.output_ids), 3), device="cuda:0")
+        amd.asnn_activate_static(onet.graph, onet.input_ids, torch.from_numpy(other.X).cuda(), oV, onet.output_ids, oY, flags=DATAFLOW)
+        amd.asnn_activate_status(amd.STATIC_SCRATCH)
