@@ -37,6 +37,7 @@ constexpr int kMaxDevices = 64;                       // per-device caches of la
 constexpr int kMixedWaves = kMixedBlock / kWave;
 constexpr int kMediumWaves = 8;                      // wavefronts per medium row in a level launch
 constexpr int kUnroll = 8;                           // row tiles in flight per wavefront
+constexpr int kXcds = 8;                             // accelerator dies: workgroup i of a launch runs on die i % 8
 
 template <int VEC> struct Vec;
 template <> struct Vec<1> { using type = float; };
@@ -286,17 +287,33 @@ __device__ inline void row_sum(const int32_t *__restrict__ col, const float *__r
 // row, which shows every tile to every XCD, costs 14 % on the 100k-node
 // workload.  Padding an odd tile count to an even one is not worth it: a
 // block that exits at once still takes a dispatch slot, and the launch rate
-// of single-wavefront blocks is within 3x of the dispatcher's.
+// of single-wavefront blocks is within 3x of the dispatcher's.  Tile counts
+// that are no multiple of 8 get the alignment from the order of the items
+// instead (items_per_xcd, below): 4-8 % on batch widths of 3, 5, 6, 7, 9, 10
+// tiles.
 template <int VEC, int LPG, typename ACC, int U>
 __global__ __launch_bounds__(kWave) void gather_light_kernel(const int32_t *__restrict__ row_ptr,
                                                                const int32_t *__restrict__ col,
                                                                const float *__restrict__ w, float *V, int B,
-                                                               int row_begin, int row_end, int tiles_per_row) {
+                                                               int row_begin, int row_end, int tiles_per_row,
+                                                               int items_per_xcd) {
     constexpr int T = LPG * VEC;                 // batch columns per tile
-    const int item = blockIdx.x;
-    const int row = row_begin + item / tiles_per_row;
-    const int tile = item % tiles_per_row;
-    if (row >= row_end) return;
+    int row, tile;
+    if (items_per_xcd == 0) {                    // tile counts that the round-robin aligns by itself
+        const int item = blockIdx.x;
+        row = row_begin + item / tiles_per_row;
+        tile = item % tiles_per_row;
+        if (row >= row_end) return;
+    } else {
+        // Any other tile count (3, 5, 6 ... tiles): the (tile, row) items in tile-major order are cut into
+        // eight equal runs and XCD x (the workgroups congruent to x modulo 8) walks run x, so that it
+        // gathers from at most two column tiles (one more per eight tiles) instead of from all of them.
+        const int rows = row_end - row_begin;
+        const long long q = (long long)(blockIdx.x % kXcds) * items_per_xcd + blockIdx.x / kXcds;
+        if (q >= (long long)rows * tiles_per_row) return;
+        tile = (int)(q / rows);
+        row = row_begin + (int)(q % rows);
+    }
     const int lane = threadIdx.x;
     const int c = tile * T + (lane % LPG) * VEC;
     const bool active = c < B;
@@ -1228,10 +1245,18 @@ int launch_level(const LevelArgs &a, int hb, int mb, int lb, int le) {
     const int tiles = (vecs + LPG - 1) / LPG;
     if (le <= hb) return ASNN_OK;
     if (lb == hb) {      // light rows only
-        const long long items = (long long)(le - lb) * tiles;
+        long long items = (long long)(le - lb) * tiles;
+        int items_per_xcd = 0;
+        if (tiles % kXcds != 0 && tiles > 1) {     // (8 | tiles: the row-major order aligns tiles and dies by itself)
+            const long long per = (items + kXcds - 1) / kXcds;
+            if (per <= 0x7fffffffLL / kXcds) {
+                items_per_xcd = (int)per;
+                items = per * kXcds;
+            }
+        }
         if (items > 0x7fffffffLL) return ASNN_ERR_SIZE;
         hipLaunchKernelGGL((gather_light_kernel<VEC, LPG, ACC, kUnroll>), dim3((unsigned)items), dim3(kWave), 0, a.s,
-                           a.row_ptr, a.col, a.w, a.V, a.B, lb, le, tiles);
+                           a.row_ptr, a.col, a.w, a.V, a.B, lb, le, tiles, items_per_xcd);
         ASNN_HIP_TRY(hipGetLastError());
         return ASNN_OK;
     }

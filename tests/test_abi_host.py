@@ -198,3 +198,24 @@ def test_static_entry_point_refuses_on_the_host(lib):
     assert lib.asnn_activate_static(ctypes.byref(rec), fake, 1, fake, 1, fake, 64, fake, fake, 0, None) == -2
     text = open(os.path.join(ROOT, "include", "asnn.h")).read()
     assert int(re.search(r"#define ASNN_STATIC_SCRATCH_BYTES \((\d+)u << 20\)", text).group(1)) << 20 == b.STATIC_SCRATCH_BYTES
+
+
+def test_compaction_and_yardstick_argument_checks_need_no_device(lib):
+    fake = ctypes.c_void_p(256)
+    n = ctypes.c_int32(-1)
+    assert lib.asnn_compact_workspace_bytes(-1) == 0
+    big = lib.asnn_compact_workspace_bytes(1000)
+    assert big > 4 * 1000 and big % 256 == 0
+    assert lib.asnn_compact_required(0, fake, fake, ctypes.byref(n), fake, 1 << 20, None) == -2
+    assert lib.asnn_compact_required(10, None, fake, ctypes.byref(n), fake, 1 << 20, None) == -1
+    assert lib.asnn_compact_required(10, fake, fake, ctypes.byref(n), fake, 16, None) == -7
+    assert lib.asnn_compact_required(10, fake, fake, ctypes.byref(n), ctypes.c_void_p(8), 1 << 20, None) == -7
+    assert lib.asnn_relabel_ids(fake, -1, fake, 10, fake, None) == -2
+    assert lib.asnn_relabel_ids(None, 5, fake, 10, fake, None) == -1
+    assert lib.asnn_relabel_ids(None, 0, None, 10, None, None) == 0
+    assert lib.asnn_device_read(None, 64, fake, None) == -1
+    assert lib.asnn_device_read(fake, 63, fake, None) == -2
+    assert lib.asnn_device_read(fake, 0, fake, None) == 0
+    assert lib.asnn_device_gather(None, 10, 64, 4, 3, 0, fake, None) == -1
+    assert lib.asnn_device_gather(fake, 10, 65, 4, 3, 0, fake, None) == -2          # rows of whole tiles only
+    assert lib.asnn_device_gather(fake, 10, 64, 0, 3, 0, fake, None) == -2
