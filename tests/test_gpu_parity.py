@@ -756,6 +756,44 @@ def test_dataflow_wait_is_bounded_and_reported(amd):
     assert torch.equal(V, good_V)
 
 
+def test_bound_call_and_yardsticks(amd):
+    """An activation whose arguments were marshalled once (Network.bind) gives the bits of the general
+    call, launch after launch, on inputs changed in place; the bandwidth yardsticks run on the value
+    matrix, read only, and leave their sink alone."""
+    wl = make_config(3, "small")
+    net = amd.Network(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.output_ids)
+    X = torch.from_numpy(wl.X).cuda()
+    for sched in (0, LEVELS, DATAFLOW, WORKGROUP):
+        want_V, want_Y = net.activate(X, flags=sched)
+        net.check(wl.B)
+        bound = net.bind(X, flags=sched)
+        for rep in range(3):
+            bound.V.fill_(float("nan"))
+            bound.Y.fill_(float("nan"))
+            bound.launch()
+            net.check(wl.B)
+            assert torch.equal(bound.V, want_V) and torch.equal(bound.Y, want_Y), (sched, rep)
+        X.mul_(0.5)                                   # the bound call reads X in place
+        bound.launch()
+        net.check(wl.B)
+        ref_V, ref_Y = net.activate(X, flags=sched)
+        net.check(wl.B)
+        assert torch.equal(bound.V, ref_V) and torch.equal(bound.Y, ref_Y), sched
+        X.copy_(torch.from_numpy(wl.X).cuda())
+    V = torch.rand((1000, 256), device="cuda:0")
+    keep = V.clone()
+    sink = torch.zeros(64, device="cuda:0")
+    amd.asnn_device_read(V, sink)
+    amd.asnn_device_gather(V, 300, 11, 7, sink)
+    amd.asnn_device_gather(V[:10, :64].contiguous(), 5, 3, 1, sink)       # one tile of 64 columns
+    W = torch.empty_like(V)
+    amd.asnn_device_copy(W, V)
+    torch.cuda.synchronize()
+    assert torch.equal(V, keep) and torch.equal(W, keep) and float(sink.abs().sum()) == 0.0
+    with pytest.raises(amd.AsnnError):
+        amd.asnn_device_gather(torch.rand((10, 65), device="cuda:0"), 5, 3, 1, sink)   # rows of whole tiles only
+
+
 def test_schedule_choice_is_reported(amd):
     wl = make_config(3, "small")
     net = amd.Network(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.output_ids)
