@@ -16,7 +16,13 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kSweepsPerSync = 64;     // frontier sweeps enqueued between two host reads
 constexpr int kGroup = 16;             // lanes that share one frontier node's out-edges
-constexpr unsigned kSweepBlocks = 512;
+// Grid-wide sweeps: 256 workgroups of 512 threads.  Larger workgroups add up more releases of a hot destination
+// before they touch its counter (a deep network with such destinations in every layer: 9.9 -> 9.0 ms against 512
+// workgroups of 256 threads; 1024 threads gain a little more there and lose 10 % where there are none).
+constexpr int kSweepThreads = 512;
+constexpr unsigned kSweepBlocks = 256;
+constexpr unsigned kReachBlocks = 512;    // the backward sweeps of the required set: workgroups of kThreads
+constexpr int kBatch = 4;              // out-edges a lane releases per round trip: a node with up to 64 takes one
 constexpr int kFoundCap = 2048;        // frontier nodes a workgroup collects in LDS before appending them
 // A destination with this many incoming connections can receive thousands of returning atomics
 // on its counter in one sweep, which serialise.  Its entries in the out-adjacency carry kHotBit, and
@@ -180,14 +186,16 @@ __device__ inline bool hot_add(int32_t u, int32_t *slot_node, int32_t *slot_coun
 // A sweep over an empty frontier does nothing, so the host may enqueue more
 // sweeps than the network has layers.
 //
-// 16 lanes share one frontier node's out-edges.  The nodes a workgroup adds to
+// 16 lanes share one frontier node's out-edges, kBatch of them per lane and round trip (with one
+// per round trip, every node with more than 16 out-edges held its layer up by a second round).  The
+// nodes a workgroup adds to
 // the next frontier are collected in LDS and appended with ONE atomic on the
 // frontier size (with tens of thousands of nodes per frontier, one atomic per
 // wavefront on that single address was most of the sweep time).  Releases of
 // hot destinations are first added up per workgroup in LDS, so such a
 // destination is decremented once per workgroup, by the number of connections
 // the workgroup's nodes send it.
-__global__ __launch_bounds__(kThreads) void sweep_kernel(int k, const int32_t *__restrict__ out_ptr,
+__global__ __launch_bounds__(kSweepThreads) void sweep_kernel(int k, const int32_t *__restrict__ out_ptr,
                                                           const int32_t *__restrict__ out_dst, int32_t *indeg,
                                                           int32_t *__restrict__ level,
                                                           const int32_t *__restrict__ frontier_in,
@@ -206,11 +214,11 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(int k, const int32_t *_
     }
     if (count == 0) return;
     int *count_out = &ctl[kCount0 + (k + 1) % 3];
-    constexpr int kNodesPerBlock = kThreads / kGroup;
+    constexpr int kNodesPerBlock = kSweepThreads / kGroup;
     const int sub = threadIdx.x % kGroup;
     const int stride = gridDim.x * kNodesPerBlock;
     if (threadIdx.x == 0) { n_found = 0; n_hot = 0; }
-    for (int i = threadIdx.x; i < kHotSlots; i += kThreads) { slot_node[i] = -1; slot_count[i] = 0; }
+    for (int i = threadIdx.x; i < kHotSlots; i += kSweepThreads) { slot_node[i] = -1; slot_count[i] = 0; }
     __syncthreads();
     auto assign = [&](int32_t u) {
         level[u] = k + 1;
@@ -220,20 +228,34 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(int k, const int32_t *_
     };
     for (int f = blockIdx.x * kNodesPerBlock + threadIdx.x / kGroup; f < count; f += stride) {
         const int32_t v = frontier_in[f];
-        const int32_t e1 = out_ptr[v + 1];
-        for (int32_t e = out_ptr[v] + sub; e < e1; e += kGroup) {
-            const int32_t raw = out_dst[e];
-            const int32_t u = raw & ~kHotBit;
-            if (raw < 0 && hot_add(u, slot_node, slot_count)) {
-                n_hot = 1;                                       // LDS, same value from every writer
-                continue;
+        const int32_t end = out_ptr[v + 1];
+        for (int32_t x = out_ptr[v] + sub; x < end; x += kGroup * kBatch) {
+            // all loads, then all decrements, then what they returned: one round trip each per kBatch
+            // out-edges (positions past the end re-read the last one and are not released)
+            int32_t raw[kBatch], old[kBatch];
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) raw[j] = out_dst[min(x + j * kGroup, end - 1)];
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {
+                old[j] = 0;
+                if (x + j * kGroup < end && raw[j] >= 0) old[j] = atomicSub(&indeg[raw[j]], 1);
             }
-            if (atomicSub(&indeg[u], 1) == 1) assign(u);
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {
+                if (x + j * kGroup >= end) continue;
+                if (raw[j] >= 0) {
+                    if (old[j] == 1) assign(raw[j]);
+                    continue;
+                }
+                const int32_t u = raw[j] & ~kHotBit;
+                if (hot_add(u, slot_node, slot_count)) n_hot = 1;            // LDS, same value from every writer
+                else if (atomicSub(&indeg[u], 1) == 1) assign(u);
+            }
         }
     }
     __syncthreads();
     if (n_hot != 0) {                                            // block-uniform
-        for (int i = threadIdx.x; i < kHotSlots; i += kThreads) {
+        for (int i = threadIdx.x; i < kHotSlots; i += kSweepThreads) {
             const int32_t u = slot_node[i];
             if (u >= 0) {
                 const int32_t c = slot_count[i];
@@ -245,7 +267,7 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(int k, const int32_t *_
     const int n = min(n_found, kFoundCap);
     if (threadIdx.x == 0 && n > 0) found_base = atomicAdd(count_out, n);
     __syncthreads();
-    for (int i = threadIdx.x; i < n; i += kThreads) frontier_out[found_base + i] = found[i];
+    for (int i = threadIdx.x; i < n; i += kSweepThreads) frontier_out[found_base + i] = found[i];
 }
 
 // Narrow frontiers.  A network with many small layers spends its sweeps on launches and on the
@@ -511,7 +533,7 @@ extern "C" int asnn_build_levels(int32_t n_nodes, int64_t n_edges, const int32_t
             for (int i = 0; i < kSweepsPerSync; ++i, ++k) {
                 const int32_t *fin = (k & 1) ? w.frontier_b : w.frontier_a;
                 int32_t *fout = (k & 1) ? w.frontier_a : w.frontier_b;
-                hipLaunchKernelGGL(sweep_kernel, dim3(kSweepBlocks), dim3(kThreads), 0, s, k, (const int32_t *)w.out_ptr,
+                hipLaunchKernelGGL(sweep_kernel, dim3(kSweepBlocks), dim3(kSweepThreads), 0, s, k, (const int32_t *)w.out_ptr,
                                    out_dst, w.indeg, level_out, fin, fout, w.ctl);
                 ASNN_HIP_TRY(hipGetLastError());
             }
@@ -690,7 +712,7 @@ extern "C" int asnn_required_set(int32_t n_nodes, int64_t n_edges, const int32_t
         for (int i = 0; i < kSweepsPerSync; ++i, ++k) {
             const int32_t *fin = (k & 1) ? w.frontier_b : w.frontier_a;
             int32_t *fout = (k & 1) ? w.frontier_a : w.frontier_b;
-            hipLaunchKernelGGL(reach_sweep_kernel, dim3(kSweepBlocks), dim3(kThreads), 0, s, k,
+            hipLaunchKernelGGL(reach_sweep_kernel, dim3(kReachBlocks), dim3(kThreads), 0, s, k,
                                (const int32_t *)w.out_ptr, in_src, required_out, fin, fout, w.ctl);
             ASNN_HIP_TRY(hipGetLastError());
         }
