@@ -274,6 +274,7 @@ def main():
     read_gbps = 4.0 * n_copy / timed(lambda: amd.asnn_device_read(ca, sink), 5) / 1e9
     del ca, cb
     gather_gbps = None
+    gather_store_gbps = None
     n_upper = wl.n_nodes - int(net.graph.level_ptr_host[3])          # rows above level 0
     if B % 64 == 0 and net.n_levels > 1 and n_upper > 0:
         # the value matrix itself is the buffer (its size and row length are the workload's); one launch per
@@ -288,6 +289,16 @@ def main():
             for lvl, (below, rows) in enumerate(shape):
                 amd.asnn_device_gather(V[:below], rows, gathers, lvl, sink)
         gather_gbps = sum(rows for _, rows in shape) * gathers * B * 4.0 / timed(gather_step, 5) / 1e9
+        # the same gathers with every row of the level stored as well (to a second matrix, so that V stays the
+        # read-only source): the traffic of a level without its arithmetic and without its graph
+        V2 = torch.empty_like(V)
+
+        def gather_store_step():
+            for lvl, (below, rows) in enumerate(shape):
+                amd.asnn_device_gather_store(V[:below], gathers, lvl, V2[below:below + rows])
+        gather_store_gbps = (sum(rows for _, rows in shape) * (gathers + 1) * B * 4.0
+                             / timed(gather_store_step, 5) / 1e9)
+        del V2
 
     for _ in range(args.warmup):
         step()
@@ -359,11 +370,14 @@ def main():
                      "device_ms_per_step_min": round(dev_ms[0], 4),
                      "device_copy_GBps": round(copy_gbps, 1), "device_read_GBps": round(read_gbps, 1),
                      "device_gather_GBps": None if gather_gbps is None else round(gather_gbps, 1),
+                     "device_gather_store_GBps": None if gather_store_gbps is None else round(gather_store_gbps, 1),
                      "frac_of_device_read": round(achieved / read_gbps, 4),
                      "frac_of_device_gather": None if gather_gbps is None else round(achieved / gather_gbps, 4),
+                     "frac_of_device_gather_store": None if gather_store_gbps is None else round(achieved / gather_store_gbps, 4),
                      "yardsticks_are": "copy: 1 GiB read + 1 GiB written; read: 1 GiB streamed; gather: one launch per level in the "
                                        "level launches' shape, every row loading the average in-degree of random rows "
-                                       "below its level from the value matrix, no arithmetic"},
+                                       "below its level from the value matrix, no arithmetic; gather_store: the same and "
+                                       "every row of the level stored too (bytes loaded + bytes stored per second)"},
     }
     if not args.no_cpu:
         import oracle

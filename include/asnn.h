@@ -344,11 +344,20 @@ int asnn_activate_static(const asnn_packed *packed,
  * when row_floats is no multiple of 128), rows_per_launch rows, each
  * wavefront loading its tile of `gathers` pseudo-random rows of buf (seeded;
  * all tiles of a row pick the same rows).  Reads
- * rows_per_launch * gathers * row_floats * 4 bytes, writes nothing. */
+ * rows_per_launch * gathers * row_floats * 4 bytes, writes nothing.
+ *
+ * asnn_device_gather_store: the same gather, and every wavefront stores its
+ * tile of one row of out[rows_per_launch][row_floats] (8-byte aligned, must
+ * not overlap buf), as a level of the activation stores the rows it
+ * computes: reads the same bytes and writes rows_per_launch * row_floats * 4.
+ * Every element of a stored row is the sum of the `gathers` elements of its
+ * column that were loaded. */
 int asnn_device_copy(void *dst, const void *src, size_t bytes, void *stream);
 int asnn_device_read(const void *src, size_t bytes, float *sink, void *stream);
 int asnn_device_gather(const float *buf, int32_t n_rows, int32_t row_floats, int32_t rows_per_launch,
                        int32_t gathers, uint32_t seed, float *sink, void *stream);
+int asnn_device_gather_store(const float *buf, int32_t n_rows, int32_t row_floats, int32_t rows_per_launch,
+                             int32_t gathers, uint32_t seed, float *out, void *stream);
 
 #ifdef __cplusplus
 }

@@ -26,6 +26,7 @@ from .binding import (  # noqa: F401
     asnn_build_levels,
     asnn_device_copy,
     asnn_device_gather,
+    asnn_device_gather_store,
     asnn_device_read,
     asnn_compact_required,
     asnn_filter_required,

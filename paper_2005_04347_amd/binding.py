@@ -41,7 +41,7 @@ EXPORTS = [
     "asnn_compact_workspace_bytes", "asnn_compact_required", "asnn_relabel_ids",
     "asnn_pack_workspace_bytes", "asnn_pack_csr", "asnn_activate_workspace_bytes", "asnn_activate",
     "asnn_activate_status", "asnn_activate_schedule", "asnn_activate_static", "asnn_device_copy",
-    "asnn_device_read", "asnn_device_gather",
+    "asnn_device_read", "asnn_device_gather", "asnn_device_gather_store",
 ]
 
 
@@ -111,6 +111,8 @@ def load() -> ctypes.CDLL:
     lib.asnn_device_read.argtypes = [vp, sz, vp, vp]
     lib.asnn_device_gather.restype = ctypes.c_int
     lib.asnn_device_gather.argtypes = [vp, i32, i32, i32, i32, u32, vp, vp]
+    lib.asnn_device_gather_store.restype = ctypes.c_int
+    lib.asnn_device_gather_store.argtypes = [vp, i32, i32, i32, i32, u32, vp, vp]
     _lib = lib
     return lib
 
@@ -403,6 +405,17 @@ def asnn_device_gather(buf: torch.Tensor, rows_per_launch: int, gathers: int, se
                                 gathers, seed, ctypes.c_void_p(sink.data_ptr()), _stream())
     if rc != 0:
         raise AsnnError(rc, "asnn_device_gather")
+
+
+def asnn_device_gather_store(buf: torch.Tensor, gathers: int, seed: int, out: torch.Tensor):
+    """The same gather, every wavefront storing its tile of one row of out (out.shape[0] rows per launch)."""
+    lib = load()
+    assert buf.dim() == 2 and buf.dtype == torch.float32 and buf.is_contiguous()
+    assert out.dim() == 2 and out.dtype == torch.float32 and out.is_contiguous() and out.shape[1] == buf.shape[1]
+    rc = lib.asnn_device_gather_store(ctypes.c_void_p(buf.data_ptr()), int(buf.shape[0]), int(buf.shape[1]),
+                                      int(out.shape[0]), gathers, seed, ctypes.c_void_p(out.data_ptr()), _stream())
+    if rc != 0:
+        raise AsnnError(rc, "asnn_device_gather_store")
 
 
 class Network:

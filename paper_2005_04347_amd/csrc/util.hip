@@ -38,14 +38,18 @@ __device__ inline uint32_t mix32(uint32_t x) {
 // per (row being computed, tile of batch columns), block index row-major, each wavefront loading
 // the same tile of `gathers` pseudo-random source rows (eight loads in flight), the 64 lanes
 // covering the tile with VEC floats each.  All tiles of one row pick the same source rows, as the
-// connections of a node do.  Only the additions that keep the loads alive are done.
-template <int VEC>
+// connections of a node do.  Only the additions that keep the loads alive are done.  With STORE
+// every wavefront also writes its tile of row item_row of `out` (out[rows of the launch][row_floats]),
+// as a level writes the rows it computes; without, `out` is the sink of a read-only kernel.
+template <int VEC, bool STORE>
 __global__ __launch_bounds__(kWave) void gather_rows_kernel(const float *__restrict__ buf, uint32_t n_rows, int row_floats,
-                                                             int tiles, int gathers, uint32_t seed, float *sink) {
+                                                             int tiles, int gathers, uint32_t seed, float *out) {
     const uint32_t item_row = blockIdx.x / (uint32_t)tiles;
     const int tile = (int)(blockIdx.x % (uint32_t)tiles);
     const float *base = buf + (size_t)tile * (kWave * VEC) + threadIdx.x * VEC;
-    float acc = 0.0f;
+    float acc[VEC];
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) acc[j] = 0.0f;
     for (int k0 = 0; k0 < gathers; k0 += 8) {
         float v[8][VEC];
 #pragma unroll
@@ -63,9 +67,40 @@ __global__ __launch_bounds__(kWave) void gather_rows_kernel(const float *__restr
 #pragma unroll
         for (int k = 0; k < 8; ++k)
 #pragma unroll
-            for (int j = 0; j < VEC; ++j) acc += v[k][j];
+            for (int j = 0; j < VEC; ++j) acc[j] += v[k][j];
     }
-    if (acc == -1.2345678e30f) sink[0] = acc;
+    if constexpr (STORE) {
+        float *q = out + (size_t)item_row * (size_t)row_floats + (size_t)tile * (kWave * VEC) + threadIdx.x * VEC;
+        if constexpr (VEC == 2) *reinterpret_cast<float2 *>(q) = make_float2(acc[0], acc[1]);
+        else *q = acc[0];
+    } else {
+        float all = 0.0f;
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) all += acc[j];
+        if (all == -1.2345678e30f) out[0] = all;
+    }
+}
+
+int launch_gather(const float *buf, int32_t n_rows, int32_t row_floats, int32_t rows_per_launch, int32_t gathers,
+                  uint32_t seed, float *out, bool store, hipStream_t s) {
+    if (!buf || !out) return ASNN_ERR_NULL;
+    if (n_rows <= 0 || row_floats <= 0 || rows_per_launch <= 0 || gathers <= 0) return ASNN_ERR_SIZE;
+    if (row_floats % kWave != 0 || ((uintptr_t)buf & 7u) != 0 || (store && ((uintptr_t)out & 7u) != 0)) return ASNN_ERR_SIZE;
+    const int vec = row_floats % (2 * kWave) == 0 ? 2 : 1;
+    const int tiles = row_floats / (kWave * vec);
+    const long long blocks = (long long)rows_per_launch * tiles;
+    if (blocks > 0x7fffffffLL) return ASNN_ERR_SIZE;
+    const dim3 grid((unsigned)blocks), block(kWave);
+    if (vec == 2 && store)
+        hipLaunchKernelGGL((gather_rows_kernel<2, true>), grid, block, 0, s, buf, (uint32_t)n_rows, row_floats, tiles, gathers, seed, out);
+    else if (vec == 2)
+        hipLaunchKernelGGL((gather_rows_kernel<2, false>), grid, block, 0, s, buf, (uint32_t)n_rows, row_floats, tiles, gathers, seed, out);
+    else if (store)
+        hipLaunchKernelGGL((gather_rows_kernel<1, true>), grid, block, 0, s, buf, (uint32_t)n_rows, row_floats, tiles, gathers, seed, out);
+    else
+        hipLaunchKernelGGL((gather_rows_kernel<1, false>), grid, block, 0, s, buf, (uint32_t)n_rows, row_floats, tiles, gathers, seed, out);
+    ASNN_HIP_TRY(hipGetLastError());
+    return ASNN_OK;
 }
 }  // namespace
 }  // namespace asnn
@@ -96,20 +131,12 @@ extern "C" int asnn_device_read(const void *src, size_t bytes, float *sink, void
 
 extern "C" int asnn_device_gather(const float *buf, int32_t n_rows, int32_t row_floats, int32_t rows_per_launch,
                                   int32_t gathers, uint32_t seed, float *sink, void *stream) {
-    if (!buf || !sink) return ASNN_ERR_NULL;
-    if (n_rows <= 0 || row_floats <= 0 || rows_per_launch <= 0 || gathers <= 0) return ASNN_ERR_SIZE;
-    if (row_floats % asnn::kWave != 0 || ((uintptr_t)buf & 7u) != 0) return ASNN_ERR_SIZE;
-    const int vec = row_floats % (2 * asnn::kWave) == 0 ? 2 : 1;
-    const int tiles = row_floats / (asnn::kWave * vec);
-    const long long blocks = (long long)rows_per_launch * tiles;
-    if (blocks > 0x7fffffffLL) return ASNN_ERR_SIZE;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    if (vec == 2)
-        hipLaunchKernelGGL(asnn::gather_rows_kernel<2>, dim3((unsigned)blocks), dim3(asnn::kWave), 0, s, buf, (uint32_t)n_rows,
-                           row_floats, tiles, gathers, seed, sink);
-    else
-        hipLaunchKernelGGL(asnn::gather_rows_kernel<1>, dim3((unsigned)blocks), dim3(asnn::kWave), 0, s, buf, (uint32_t)n_rows,
-                           row_floats, tiles, gathers, seed, sink);
-    ASNN_HIP_TRY(hipGetLastError());
-    return ASNN_OK;
+    return asnn::launch_gather(buf, n_rows, row_floats, rows_per_launch, gathers, seed, sink, false,
+                               static_cast<hipStream_t>(stream));
+}
+
+extern "C" int asnn_device_gather_store(const float *buf, int32_t n_rows, int32_t row_floats, int32_t rows_per_launch,
+                                        int32_t gathers, uint32_t seed, float *out, void *stream) {
+    return asnn::launch_gather(buf, n_rows, row_floats, rows_per_launch, gathers, seed, out, true,
+                               static_cast<hipStream_t>(stream));
 }

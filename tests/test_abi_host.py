@@ -219,3 +219,6 @@ def test_compaction_and_yardstick_argument_checks_need_no_device(lib):
     assert lib.asnn_device_gather(None, 10, 64, 4, 3, 0, fake, None) == -1
     assert lib.asnn_device_gather(fake, 10, 65, 4, 3, 0, fake, None) == -2          # rows of whole tiles only
     assert lib.asnn_device_gather(fake, 10, 64, 0, 3, 0, fake, None) == -2
+    assert lib.asnn_device_gather_store(fake, 10, 64, 4, 3, 0, None, None) == -1
+    assert lib.asnn_device_gather_store(fake, 10, 64, 4, 0, 0, fake, None) == -2
+    assert lib.asnn_device_gather_store(fake, 10, 128, 4, 3, 0, ctypes.c_void_p(4100), None) == -2     # out is stored 8 bytes at a time

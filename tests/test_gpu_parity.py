@@ -792,6 +792,23 @@ def test_bound_call_and_yardsticks(amd):
     assert torch.equal(V, keep) and torch.equal(W, keep) and float(sink.abs().sum()) == 0.0
     with pytest.raises(amd.AsnnError):
         amd.asnn_device_gather(torch.rand((10, 65), device="cuda:0"), 5, 3, 1, sink)   # rows of whole tiles only
+    # the gather that also stores: every element of a stored row is the sum of what its column loaded, all
+    # tiles of a row load the same rows, the source stays as it was, and nothing beyond the rows asked for is written
+    for cols in (256, 192, 64):
+        rows_of = torch.arange(1000, device="cuda:0", dtype=torch.float32)
+        S = rows_of[:, None].expand(1000, cols).contiguous()
+        out = torch.full((301, cols), -1.0, device="cuda:0")
+        amd.asnn_device_gather_store(S, 11, 7, out[:300])
+        torch.cuda.synchronize()
+        assert torch.equal(S, rows_of[:, None].expand(1000, cols)) and bool((out[300] == -1.0).all())
+        got = out[:300]
+        assert bool((got == got[:, :1]).all())                      # one sum per row, in every column of every tile
+        assert bool((got >= 0).all()) and bool((got <= 11 * 999).all()) and bool((got == got.round()).all())
+        assert got[:, 0].unique().numel() > 250                     # different rows gather different sources
+        ones = torch.ones((1000, cols), device="cuda:0")
+        amd.asnn_device_gather_store(ones, 11, 3, out[:300])
+        torch.cuda.synchronize()
+        assert bool((out[:300] == 11.0).all())
 
 
 def test_schedule_choice_is_reported(amd):
