@@ -547,6 +547,36 @@ def test_levels_across_narrow_and_wide_frontiers(amd, seed):
     assert e.value.code == -6
 
 
+@pytest.mark.parametrize("block", [1, 1500])
+def test_levels_with_out_degrees_around_the_sweep_batches(amd, block):
+    """The grid-wide sweeps release a node's outgoing connections 16 lanes x 4 at a time: out-degrees on
+    both sides of every multiple of 16 up to 64 and of 64 beyond, in a random DAG over a topological order
+    cut into blocks of `block` nodes, every connection leading into one of the next three blocks (1: thousands
+    of layers of a few nodes, the single workgroup's sweeps after a grid-wide start; 1500: a dozen layers of
+    some 1500 nodes, grid-wide sweeps throughout).  Bit-exact."""
+    rng = np.random.default_rng(17 + block)
+    n = 20000
+    degrees = np.array([0, 1, 15, 16, 17, 31, 32, 33, 47, 48, 49, 63, 64, 65, 127, 128, 129, 200, 257])
+    src, dst = [], []
+    for i in range(n):
+        d = int(degrees[rng.integers(0, len(degrees))])
+        lo = (i // block + 1) * block
+        hi = min(n, lo + 3 * block)
+        if d and lo < hi:
+            src.append(np.full(d, i, np.int32))
+            dst.append(rng.integers(lo, hi, size=d).astype(np.int32))
+    src, dst = np.concatenate(src), np.concatenate(dst)
+    relabel = rng.permutation(n).astype(np.int32)
+    order = rng.permutation(len(src))
+    src, dst = relabel[src][order], relabel[dst][order]
+    assert len(src) > 1_000_000
+    want, want_levels = oracle.levels(n, src, dst)
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    got, n_levels = amd.asnn_build_levels(n, t(src), t(dst), t(np.zeros(0, np.int32)))
+    assert n_levels == want_levels
+    assert np.array_equal(got.cpu().numpy(), want)
+
+
 def test_levels_of_a_very_deep_network(amd):
     """4500 layers of one to three nodes behind two wide ones: the sweeps change from the grid-wide
     kernel to the single workgroup that runs sweep after sweep on the device, whose count of sweeps is
