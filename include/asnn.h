@@ -97,6 +97,10 @@ extern "C" {
 #define ASNN_MEDIUM_INDEGREE 32
 #define ASNN_CLASSES 3
 
+/* Largest connection count any call takes (32-bit positions, with headroom for
+ * the kernels' look-ahead past a position): 2^31 - 65536.  More: ASNN_ERR_SIZE. */
+#define ASNN_MAX_EDGES 2147418112LL
+
 const char *asnn_strerror(int code);
 int asnn_last_hip_error(void);
 int asnn_version(void);
@@ -109,7 +113,7 @@ int asnn_version(void);
  *   level_out    device int32[n_nodes]   receives the level of every node
  *   n_levels_out host   int32*           receives max level + 1 (0 if n_nodes == 0)
  *   workspace    device, >= asnn_levels_workspace_bytes(), 256-byte aligned
- * Errors: NULL, SIZE (n_nodes < 0, n_edges < 0 or >= 2^31), INDEX,
+ * Errors: NULL, SIZE (n_nodes < 0, n_edges < 0 or > ASNN_MAX_EDGES), INDEX,
  * INPUT_HAS_INEDGE, DUP_INPUT, CYCLE (level_out is then unspecified),
  * WORKSPACE, HIP.  Blocks until the result is known. */
 size_t asnn_levels_workspace_bytes(int32_t n_nodes, int64_t n_edges);

@@ -491,7 +491,7 @@ extern "C" size_t asnn_levels_workspace_bytes(int32_t n_nodes, int64_t n_edges) 
 extern "C" int asnn_build_levels(int32_t n_nodes, int64_t n_edges, const int32_t *src, const int32_t *dst,
                                  const int32_t *input_ids, int32_t n_inputs, int32_t *level_out, int32_t *n_levels_out,
                                  void *workspace, size_t workspace_bytes, void *stream) {
-    if (n_nodes < 0 || n_edges < 0 || n_edges >= (int64_t)INT32_MAX || n_inputs < 0) return ASNN_ERR_SIZE;
+    if (n_nodes < 0 || n_edges < 0 || n_edges > (int64_t)ASNN_MAX_EDGES || n_inputs < 0) return ASNN_ERR_SIZE;
     if (!n_levels_out) return ASNN_ERR_NULL;
     if (n_nodes == 0) {
         if (n_edges > 0 || n_inputs > 0) return ASNN_ERR_INDEX;
@@ -690,7 +690,7 @@ extern "C" size_t asnn_required_workspace_bytes(int32_t n_nodes, int64_t n_edges
 extern "C" int asnn_required_set(int32_t n_nodes, int64_t n_edges, const int32_t *src, const int32_t *dst,
                                  const int32_t *output_ids, int32_t n_outputs, int32_t *required_out,
                                  int32_t *n_required_out, void *workspace, size_t workspace_bytes, void *stream) {
-    if (n_nodes <= 0 || n_edges < 0 || n_edges >= (int64_t)INT32_MAX || n_outputs < 0) return ASNN_ERR_SIZE;
+    if (n_nodes <= 0 || n_edges < 0 || n_edges > (int64_t)ASNN_MAX_EDGES || n_outputs < 0) return ASNN_ERR_SIZE;
     if (!required_out || !n_required_out || !workspace) return ASNN_ERR_NULL;
     if ((n_edges > 0 && (!src || !dst)) || (n_outputs > 0 && !output_ids)) return ASNN_ERR_NULL;
     if (((uintptr_t)workspace & 255u) != 0 || workspace_bytes < asnn_required_workspace_bytes(n_nodes, n_edges))
@@ -735,7 +735,7 @@ extern "C" int asnn_filter_required(int32_t n_nodes, int64_t n_edges, const int3
                                     const float *w, const int32_t *required, int32_t *src_out, int32_t *dst_out,
                                     float *w_out, int64_t *n_kept_out, void *workspace, size_t workspace_bytes,
                                     void *stream) {
-    if (n_nodes <= 0 || n_edges < 0 || n_edges >= (int64_t)INT32_MAX) return ASNN_ERR_SIZE;
+    if (n_nodes <= 0 || n_edges < 0 || n_edges > (int64_t)ASNN_MAX_EDGES) return ASNN_ERR_SIZE;
     if (!required || !n_kept_out || !workspace) return ASNN_ERR_NULL;
     if (n_edges > 0 && (!src || !dst || !w || !src_out || !dst_out || !w_out)) return ASNN_ERR_NULL;
     if (((uintptr_t)workspace & 255u) != 0 || workspace_bytes < asnn_filter_workspace_bytes(n_edges))

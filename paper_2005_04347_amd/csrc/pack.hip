@@ -245,7 +245,7 @@ extern "C" int asnn_pack_csr(const int32_t *src, const int32_t *dst, const float
     int32_t *level_ptr = packed->level_ptr, *level_ptr_host = packed->level_ptr_host, *perm = packed->perm,
             *inv_perm = packed->inv_perm, *row_ptr = packed->row_ptr, *col = packed->col, *unit_ptr = packed->unit_ptr;
     float *w_packed = packed->w;
-    if (n_nodes <= 0 || n_edges < 0 || n_edges >= (int64_t)INT32_MAX || n_levels <= 0 ||
+    if (n_nodes <= 0 || n_edges < 0 || n_edges > (int64_t)ASNN_MAX_EDGES || n_levels <= 0 ||
         n_levels > n_nodes || n_levels >= (1 << 28))
         return ASNN_ERR_SIZE;
     if (!level || !level_ptr || !level_ptr_host || !perm || !inv_perm || !row_ptr || !unit_ptr || !workspace)

@@ -78,6 +78,9 @@ def test_argument_checks_need_no_device(lib):
     assert lib.asnn_build_levels(-1, 0, None, None, None, 0, fake, ctypes.byref(nl), fake, 1 << 20, None) == -2
     assert lib.asnn_build_levels(4, -1, None, None, None, 0, fake, ctypes.byref(nl), fake, 1 << 20, None) == -2
     assert lib.asnn_build_levels(4, 2**31, fake, fake, None, 0, fake, ctypes.byref(nl), fake, 1 << 20, None) == -2
+    assert lib.asnn_build_levels(4, 2**31 - 65535, fake, fake, None, 0, fake, ctypes.byref(nl), fake, 1 << 20, None) == -2
+    # the largest count that is taken fails on the workspace, not on the size
+    assert lib.asnn_build_levels(4, 2**31 - 65536, fake, fake, None, 0, fake, ctypes.byref(nl), ctypes.c_void_p(256), 1 << 20, None) == -7
     assert lib.asnn_build_levels(4, 2, None, fake, None, 0, fake, ctypes.byref(nl), fake, 1 << 20, None) == -1
     assert lib.asnn_build_levels(4, 2, fake, fake, None, 1, fake, ctypes.byref(nl), fake, 1 << 20, None) == -1
     assert lib.asnn_build_levels(4, 2, fake, fake, None, 0, fake, ctypes.byref(nl), None, 1 << 20, None) == -1
