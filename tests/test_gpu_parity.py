@@ -642,6 +642,23 @@ def test_full_size_configs(amd, idx):
         del V, Y
 
 
+def test_full_size_benchmark_workload_in_the_fast_mode(amd):
+    """The benchmark workload with fp32 sums (ASNN_FLAG_ACC_F32, the mode `bench.py --flags 2` times): every
+    element of the value matrix within the same 1e-5 of the oracle, in the level launches and the dataflow
+    schedule (the deep and the population workloads do not meet the bound with fp32 sums, which is why
+    fp64 sums are the default and this mode makes no claim there)."""
+    wl = make_config(3, "full")
+    net = amd.Network(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.output_ids)
+    want = oracle.activate(wl.n_nodes, wl.src, wl.dst, wl.w, wl.input_ids, wl.X)
+    inv = net.graph.inv_perm.long()
+    for sched in (0, DATAFLOW):
+        _, V, _ = run_gpu(amd, wl, flags=sched | amd.FLAG_ACC_F32, net=net)
+        err, any_nan = _max_abs_err_every_element(V, inv, want)
+        print(f"config 3 fast mode schedule {sched}: max_abs_err={err:.3e}")
+        assert not any_nan and err <= TOL, (sched, err)
+        del V
+
+
 def _per_network(wl, k):
     """Network k of a population workload as a workload of its own (ids and rows made local)."""
     from workloads import Workload
