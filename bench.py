@@ -192,7 +192,8 @@ def main():
     ap.add_argument("--schedule", choices=["auto", "levels", "dataflow", "workgroup"], default="auto",
                     help="level launches, persistent dataflow launch, or the library's own choice")
     ap.add_argument("--graph", action="store_true", help="capture one asnn_activate in a HIP graph and time replays")
-    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-cpu", action="store_true",
+                    help="the timed activation and its yardsticks only: skip the cpu_baseline leg and the fp32-sum side timing")
     ap.add_argument("--regime-quick", action="store_true", help="with --paper-regime: three networks only (for profiling)")
     ap.add_argument("--paper-regime", action="store_true",
                     help="batch-1 latency against connections, as in the paper's figures (prints one line per network)")
@@ -326,7 +327,7 @@ def main():
     # beside it, not as the result: the same activation with fp32 sums (the paper's Float; the mode keeps the
     # parity bound on the 100k-node workload only, see tests/test_gpu_parity.py)
     fp32_ms = None
-    if (flags & amd.FLAG_ACC_F32) == 0 and not args.graph:
+    if (flags & amd.FLAG_ACC_F32) == 0 and not args.graph and not args.no_cpu:
         fast_step = net.bind(X, V=V, Y=Y, flags=flags | amd.FLAG_ACC_F32).launch
         for _ in range(3):
             fast_step()
